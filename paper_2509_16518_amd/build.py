@@ -1,0 +1,38 @@
+"""In-tree builds: the HIP C-ABI library (hipcc, gfx950) and the input-generator library (gcc)."""
+import os
+import subprocess
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+REPO_DIR = os.path.dirname(PKG_DIR)
+CSRC = os.path.join(PKG_DIR, "csrc")
+LIBFGATTN = os.path.join(PKG_DIR, "libfgattn.so")
+LIBFGW = os.path.join(PKG_DIR, "workloads", "libfgw.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+HIP_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wno-unused-command-line-argument",
+]
+
+
+def _run(cmd):
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("build failed: %s\n%s" % (" ".join(cmd), r.stdout))
+    return r.stdout
+
+
+def build_workloads(force=True):
+    src = os.path.join(PKG_DIR, "workloads", "fgw_gen.c")
+    if force or not os.path.exists(LIBFGW):
+        _run(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", src, "-o", LIBFGW, "-lm"])
+    return LIBFGW
+
+
+def build_hip(force=True, extra_flags=()):
+    srcs = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".hip")]
+    if force or not os.path.exists(LIBFGATTN):
+        _run([HIPCC] + HIP_FLAGS + list(extra_flags) + ["-I", os.path.join(REPO_DIR, "include"), "-I", CSRC]
+             + srcs + ["-o", LIBFGATTN])
+    return LIBFGATTN
