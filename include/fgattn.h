@@ -1,0 +1,112 @@
+/*
+ * fgattn.h -- C ABI of the MI355X (gfx950) forward kernel for fine-grained sparse attention.
+ *
+ * What it computes (paper Sec. 2 "Efficient dense attention" / "Efficient block sparse
+ * attention", Sec. 4.1 and Fig. 1b): per batch b, head h and query block i (rows
+ * [i*M, min((i+1)*M, L))), softmax(scale * Q K^T) restricted to the keys of the active
+ * key groups listed for that block, times V.  A key group g covers keys
+ * [g*N, min((g+1)*N, L)).  A skipped key takes no part in the softmax.
+ *
+ * All tensor and mask pointers are DEVICE pointers owned by the caller.  The library
+ * allocates no device memory; scratch space (work order + queue counter) is the
+ * caller-provided `workspace` of at least fgattn_workspace_bytes() bytes, 256-byte aligned.
+ * Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = default stream)
+ * and never synchronise the host, except fgattn_validate_mask.  Two calls that share a
+ * workspace must be ordered on one stream.
+ *
+ * Return value: 0 (FGATTN_OK) or a negative FGATTN_E* code; fgattn_strerror() names it.
+ * No C++ exceptions cross this boundary.
+ */
+#ifndef FGATTN_H_
+#define FGATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  FGATTN_OK = 0,
+  FGATTN_E_NULL = -1,        /* a required pointer is NULL */
+  FGATTN_E_SHAPE = -2,       /* B,H,L < 1; d not in {64,128}; M not in {16,32,64,128}; N < 1; L+N overflows int32 */
+  FGATTN_E_STRIDE = -3,      /* a row stride is not a multiple of 8 elements, or smaller than d */
+  FGATTN_E_ALIGN = -4,       /* q/k/v/out not 16-byte aligned, or workspace not 256-byte aligned */
+  FGATTN_E_WORKSPACE = -5,   /* workspace_bytes too small */
+  FGATTN_E_SCALE = -6,       /* scale is not finite */
+  FGATTN_E_DEVICE = -7,      /* not a gfx950 device, or a HIP runtime call failed */
+  FGATTN_E_MASK = -8,        /* fgattn_validate_mask found a bad mask */
+  FGATTN_E_FLAGS = -9        /* unknown flag bits */
+};
+
+enum {
+  /* Scheduling of work items (one item = one query block of one head) onto the persistent
+   * workgroups; paper Sec. 4.2 "Load balancing" and Appendix B.  Default (0): per head, items
+   * ordered by decreasing active-list length and fetched from a device-side queue. */
+  FGATTN_FLAG_STATIC_ASSIGN = 1,  /* ablation "no scheduler": item j goes to workgroup j mod grid, natural order */
+  FGATTN_FLAG_FIFO_QUEUE = 2,     /* device-side queue, but natural order (no longest-first ordering) */
+  FGATTN_FLAG_REUSE_PLAN = 4      /* skip the ordering pre-pass: `workspace` already holds the order built by an
+                                     earlier fgattn_forward/fgattn_plan call for the same mask and params */
+};
+
+typedef struct fgattn_params {
+  int32_t B, H, L, d;            /* batch, heads, tokens, head dim (64 or 128) */
+  int32_t M, N;                  /* query-block rows (16, 32, 64 or 128); keys per key group (>= 1) */
+  /* strides in ELEMENTS (bf16); the last dimension (d) is contiguous; row strides must be multiples of 8 */
+  int64_t q_stride_b, q_stride_h, q_stride_l;
+  int64_t k_stride_b, k_stride_h, k_stride_l;
+  int64_t v_stride_b, v_stride_h, v_stride_l;
+  int64_t o_stride_b, o_stride_h, o_stride_l;
+  float scale;                   /* multiplies Q K^T; the paper uses 1/sqrt(d) (Sec. 2) */
+  int32_t flags;                 /* FGATTN_FLAG_* */
+} fgattn_params;
+
+/* Bytes of device workspace fgattn_forward / fgattn_dense_forward / fgattn_plan need for `p`
+ * (0 if p is NULL or its shape is invalid). */
+size_t fgattn_workspace_bytes(const fgattn_params* p);
+
+/*
+ * Sparse forward pass (paper Sec. 4.1 gather-load + Sec. 4.2 / Appendix B scheduler).
+ *   q, k, v      : bf16, logical shape [B, H, L, d], addressed through the strides in `p`.
+ *   mask_indptr  : int64 [B*H*ceil(L/M) + 1], non-decreasing, mask_indptr[0] == 0.  Work item
+ *                  w = (b*H + h)*ceil(L/M) + i owns mask_indices[mask_indptr[w] : mask_indptr[w+1]].
+ *   mask_indices : int32 key-GROUP ids in [0, ceil(L/N)); any order; no duplicates within an item.
+ *                  Contents are NOT checked here (out-of-range ids are undefined behaviour);
+ *                  use fgattn_validate_mask in tests.
+ *   out          : bf16, same logical shape as q (strides o_stride_*).  Rows >= L are not written.
+ *   lse          : fp32 [B, H, L] contiguous: natural-log of sum_k exp(scale * q.k) over the active
+ *                  keys; an item with an empty list gets out = 0 and lse = -inf.
+ * Enqueues an ordering pre-pass (unless FGATTN_FLAG_REUSE_PLAN) and one persistent kernel.
+ */
+int fgattn_forward(const void* q, const void* k, const void* v, const int64_t* mask_indptr,
+                   const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* workspace,
+                   size_t workspace_bytes, void* stream);
+
+/* Dense attention (0% sparsity: every key active), the comparison kernel of the same build
+ * (paper Sec. 2 "Efficient dense attention").  Same arguments minus the mask; p->N is ignored. */
+int fgattn_dense_forward(const void* q, const void* k, const void* v, const fgattn_params* p, void* out, float* lse,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Only the ordering pre-pass of fgattn_forward (Appendix B: cost of an item = length of its
+ * key/value list; longest first): fills `workspace`.  A later fgattn_forward with
+ * FGATTN_FLAG_REUSE_PLAN and the same mask/params skips it. */
+int fgattn_plan(const int64_t* mask_indptr, const fgattn_params* p, void* workspace, size_t workspace_bytes,
+                void* stream);
+
+/* Slow, SYNCHRONOUS check of a device-resident mask: indptr starts at 0 and is non-decreasing,
+ * every id is in [0, ceil(L/N)), no id repeats within an item.  Uses the first 256 bytes of
+ * `workspace`.  Returns FGATTN_OK or FGATTN_E_MASK. */
+int fgattn_validate_mask(const int64_t* mask_indptr, const int32_t* mask_indices, const fgattn_params* p,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Number of persistent workgroups fgattn_forward would launch for `p` on the current device
+ * (0 on error).  Informational: used by benchmarks to report the launch shape. */
+int fgattn_grid_size(const fgattn_params* p);
+
+const char* fgattn_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FGATTN_H_ */

@@ -31,8 +31,17 @@ def build_workloads(force=True):
 
 
 def build_hip(force=True, extra_flags=()):
+    """Compile every .hip translation unit for gfx950 (in parallel) and link libfgattn.so in-tree."""
+    from concurrent.futures import ThreadPoolExecutor
     srcs = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".hip")]
-    if force or not os.path.exists(LIBFGATTN):
-        _run([HIPCC] + HIP_FLAGS + list(extra_flags) + ["-I", os.path.join(REPO_DIR, "include"), "-I", CSRC]
-             + srcs + ["-o", LIBFGATTN])
+    if not force and os.path.exists(LIBFGATTN):
+        return LIBFGATTN
+    objdir = os.path.join(PKG_DIR, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    common = [f for f in HIP_FLAGS if f != "-shared"] + list(extra_flags) + \
+        ["-I", os.path.join(REPO_DIR, "include"), "-I", CSRC]
+    objs = [os.path.join(objdir, os.path.basename(s)[:-4] + ".o") for s in srcs]
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+        list(ex.map(lambda so: _run([HIPCC] + common + ["-c", so[0], "-o", so[1]]), zip(srcs, objs)))
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIBFGATTN])
     return LIBFGATTN

@@ -1,0 +1,35 @@
+// Kernel argument block shared by the host-side launcher and the forward kernel.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fg {
+
+struct FwdArgs {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  uint16_t* out;
+  float* lse;
+  const int64_t* indptr;   // null => dense: every key of [0, L) in order
+  const int32_t* indices;
+  const int32_t* order;    // work-item ids in processing order
+  int32_t* counter;        // queue head (zeroed by the pre-pass)
+  int64_t q_sb, q_sh, q_sl, k_sb, k_sh, k_sl, v_sb, v_sh, v_sl, o_sb, o_sh, o_sl;  // elements
+  int32_t H, L, M, N, nshift, QB, n_items, static_assign;
+  float c_log2;      // |scale| * log2(e): exp(scale*s) == exp2(c_log2 * s')
+  float scale_abs;   // |scale|
+  uint32_t q_sign;   // 0x80008000 if scale < 0 (the sign is moved onto Q, exactly), else 0
+};
+
+// Launches the forward kernel variant for (a.M, d) on `stream` with a persistent grid sized to
+// the device (`cus` compute units).  If grid_only != nullptr nothing is launched and the grid
+// size is stored there.  Returns an FGATTN_* code.
+int launch_forward(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only);
+
+// One translation unit per query-tile size keeps compile times parallel.
+int launch_mt32(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only);
+int launch_mt64(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only);
+int launch_mt128(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only);
+
+}  // namespace fg

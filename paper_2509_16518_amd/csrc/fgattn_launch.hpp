@@ -1,0 +1,35 @@
+// Host-side launcher template: occupancy-sized persistent grid, opt-in to large dynamic LDS.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "fgattn.h"
+#include "fgattn_args.hpp"
+
+namespace fg {
+
+template <typename Kernel>
+int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipStream_t stream, int* grid_only,
+                   int* occ_cache) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
+  if (occ_cache[dev] == 0) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            lds_bytes) != hipSuccess)
+      return FGATTN_E_DEVICE;
+    int occ = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, 256, lds_bytes) != hipSuccess || occ < 1)
+      return FGATTN_E_DEVICE;
+    occ_cache[dev] = occ;
+  }
+  long long want = (long long)cus * occ_cache[dev];
+  int grid = (int)(a.n_items < want ? a.n_items : want);
+  if (grid < 1) grid = 1;
+  if (grid_only) {
+    *grid_only = grid;
+    return FGATTN_OK;
+  }
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds_bytes, stream, a);
+  return hipGetLastError() == hipSuccess ? FGATTN_OK : FGATTN_E_DEVICE;
+}
+
+}  // namespace fg
