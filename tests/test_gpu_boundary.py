@@ -1,0 +1,62 @@
+"""Error behaviour of the C ABI on a GPU machine: bad arguments come back as codes, nothing is launched."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_16518_amd import fgattn as F
+from paper_2509_16518_amd import workloads as W
+from gpu_util import Problem
+
+pytestmark = pytest.mark.gpu
+
+
+def expect(code, fn):
+    with pytest.raises(F.FgattnError) as e:
+        fn()
+    assert e.value.code == code, (e.value.code, code)
+
+
+def test_argument_errors():
+    prob = Problem(W.TINY)
+    p = prob.params()
+    ws = prob.workspace(p)
+    call = lambda pp, w=ws, q=None: F.fgattn_forward(q if q is not None else prob.q, prob.k, prob.v, prob.d_indptr,
+                                                     prob.d_indices, pp, prob.out, prob.lse, w)
+    bad = prob.params(); bad.d = 96
+    expect(F.E_SHAPE, lambda: call(bad))
+    bad = prob.params(); bad.M = 48
+    expect(F.E_SHAPE, lambda: call(bad))
+    bad = prob.params(); bad.N = 0
+    expect(F.E_SHAPE, lambda: call(bad))
+    bad = prob.params(); bad.q_stride_l = 60
+    expect(F.E_STRIDE, lambda: call(bad))
+    bad = prob.params(); bad.scale = float("inf")
+    expect(F.E_SCALE, lambda: call(bad))
+    bad = prob.params(); bad.flags = 64
+    expect(F.E_FLAGS, lambda: call(bad))
+    expect(F.E_WORKSPACE, lambda: call(p, ws[:256]))
+    expect(F.E_ALIGN, lambda: call(p, ws[16:]))
+    qoff = prob.q.view(-1)[4:]                                  # 8-byte offset: not 16-byte aligned
+    rc = F.lib().fgattn_forward(qoff.data_ptr(), prob.k.data_ptr(), prob.v.data_ptr(), prob.d_indptr.data_ptr(),
+                                prob.d_indices.data_ptr(), ctypes.byref(p), prob.out.data_ptr(), prob.lse.data_ptr(),
+                                ws.data_ptr(), ws.numel(), None)
+    assert rc == F.E_ALIGN
+    assert F.lib().fgattn_forward(None, None, None, None, None, None, None, None, None, 0, None) == F.E_NULL
+    assert "workspace" in F.fgattn_strerror(F.E_WORKSPACE)
+
+
+def test_validate_mask_flags_bad_masks():
+    prob = Problem(W.TINY)
+    p = prob.params()
+    ws = prob.workspace(p)
+    assert F.fgattn_validate_mask(prob.d_indptr, prob.d_indices, p, ws) == 0
+    dup = prob.d_indices.clone(); dup[1] = dup[0]
+    assert F.fgattn_validate_mask(prob.d_indptr, dup, p, ws) == F.E_MASK
+    oob = prob.d_indices.clone(); oob[5] = prob.w.G
+    assert F.fgattn_validate_mask(prob.d_indptr, oob, p, ws) == F.E_MASK
+    neg = prob.d_indices.clone(); neg[7] = -1
+    assert F.fgattn_validate_mask(prob.d_indptr, neg, p, ws) == F.E_MASK
+    dec = prob.d_indptr.clone(); dec[3] = dec[2] - 1
+    assert F.fgattn_validate_mask(dec, prob.d_indices, p, ws) == F.E_MASK
