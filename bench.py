@@ -66,8 +66,10 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="wan-1.3b", choices=["wan-1.3b", "tiny"])
-    ap.add_argument("--cpu-items", type=int, default=96, help="work items the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-items", type=int, default=1536, help="work items the oracle is timed on (0 = skip)")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy kernel (reference for scaling rocprofv3 FETCH/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (heads and query blocks shard with no "
@@ -106,6 +108,13 @@ def main():
     def main_kernel_only():
         F.fgattn_forward(dq, dk, dv, d_indptr, d_indices, p_reuse, out, lse, ws)
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     log("timing %d steps after %d warm-up" % (args.steps, args.warmup))
     torch.cuda.synchronize()
     t0 = time.perf_counter()

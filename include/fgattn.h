@@ -30,8 +30,10 @@ extern "C" {
 enum {
   FGATTN_OK = 0,
   FGATTN_E_NULL = -1,        /* a required pointer is NULL */
-  FGATTN_E_SHAPE = -2,       /* B,H,L < 1; d not in {64,128}; M not in {16,32,64,128}; N < 1; L+N overflows int32 */
-  FGATTN_E_STRIDE = -3,      /* a row stride is not a multiple of 8 elements, or smaller than d */
+  FGATTN_E_SHAPE = -2,       /* B,H,L < 1; L > 2^24; d not in {64,128}; M not in {16,32,64,128}; N < 1;
+                                L+N overflows int32 */
+  FGATTN_E_STRIDE = -3,      /* a stride is not a multiple of 8 elements, a row stride is smaller than d, or a K/V
+                                (batch, head) slice spans 4 GiB or more, or a row stride is 16 MiB or more */
   FGATTN_E_ALIGN = -4,       /* q/k/v/out not 16-byte aligned, or workspace not 256-byte aligned */
   FGATTN_E_WORKSPACE = -5,   /* workspace_bytes too small */
   FGATTN_E_SCALE = -6,       /* scale is not finite */

@@ -146,6 +146,7 @@ static int check_shape(const fgattn_params* p) {
   if (p->d != 64 && p->d != 128) return FGATTN_E_SHAPE;
   if (p->M != 16 && p->M != 32 && p->M != 64 && p->M != 128) return FGATTN_E_SHAPE;
   if ((int64_t)p->L + p->N > 0x7fffffffLL) return FGATTN_E_SHAPE;
+  if (p->L > (1 << 24)) return FGATTN_E_SHAPE;   // key row * row bytes uses 24-bit multiplies
   if (n_items_of(p) > 0x7fffffffLL) return FGATTN_E_SHAPE;
   if (p->flags & ~(FGATTN_FLAG_STATIC_ASSIGN | FGATTN_FLAG_FIFO_QUEUE | FGATTN_FLAG_REUSE_PLAN)) return FGATTN_E_FLAGS;
   return FGATTN_OK;
@@ -156,7 +157,7 @@ static int check_tensors(const void* q, const void* k, const void* v, const void
   if (!q || !k || !v || !out || !lse) return FGATTN_E_NULL;
   const int64_t rows[4] = {p->q_stride_l, p->k_stride_l, p->v_stride_l, p->o_stride_l};
   for (int i = 0; i < 4; i++)
-    if (rows[i] < p->d || (rows[i] % 8) != 0) return FGATTN_E_STRIDE;
+    if (rows[i] < p->d || (rows[i] % 8) != 0 || rows[i] * 2 >= (1 << 24)) return FGATTN_E_STRIDE;
   const int64_t outer[8] = {p->q_stride_b, p->q_stride_h, p->k_stride_b, p->k_stride_h,
                             p->v_stride_b, p->v_stride_h, p->o_stride_b, p->o_stride_h};
   for (int i = 0; i < 8; i++)
@@ -165,6 +166,10 @@ static int check_tensors(const void* q, const void* k, const void* v, const void
   for (int i = 0; i < 4; i++)
     if ((reinterpret_cast<uintptr_t>(ptrs[i]) & 15) != 0) return FGATTN_E_ALIGN;
   if ((reinterpret_cast<uintptr_t>(lse) & 3) != 0) return FGATTN_E_ALIGN;
+  // the gather addresses K/V rows with 32-bit byte offsets from the (batch, head) slice base
+  const int64_t last = (int64_t)p->L - 1;
+  if (last * p->k_stride_l * 2 + 2 * p->d > 0xffffffffLL || last * p->v_stride_l * 2 + 2 * p->d > 0xffffffffLL)
+    return FGATTN_E_STRIDE;
   if (!isfinite(p->scale)) return FGATTN_E_SCALE;
   return FGATTN_OK;
 }
@@ -220,9 +225,10 @@ static int run_forward(const void* q, const void* k, const void* v, const int64_
   a.L = p->L;
   a.M = p->M;
   a.N = indptr ? p->N : 1;
-  a.nshift = -1;
-  for (int s = 0; s < 31; s++)
-    if ((1 << s) == a.N) a.nshift = s;
+  const int NT = p->M <= 32 ? 128 : p->M == 64 ? 64 : 32;   // keys per LDS tile of the variant launched for M
+  a.nt_div_n = NT / a.N;
+  a.nt_mod_n = NT % a.N;
+  a.n_recip16 = (65536u + (uint32_t)a.N - 1) / (uint32_t)a.N;
   a.QB = (p->L + p->M - 1) / p->M;
   a.n_items = (int32_t)n_items_of(p);
   a.static_assign = (p->flags & FGATTN_FLAG_STATIC_ASSIGN) ? 1 : 0;
@@ -298,6 +304,7 @@ int fgattn_grid_size(const fgattn_params* p) {
   memset(&a, 0, sizeof(a));
   a.M = p->M;
   a.n_items = (int32_t)fg::n_items_of(p);
+  a.indptr = reinterpret_cast<const int64_t*>(&a);   // any non-null value: report the sparse variant's grid
   int grid = 0;
   if (fg::launch_forward(a, p->d, dev.cus, nullptr, &grid) != FGATTN_OK) return 0;
   return grid;

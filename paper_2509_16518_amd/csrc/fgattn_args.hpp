@@ -16,7 +16,10 @@ struct FwdArgs {
   const int32_t* order;    // work-item ids in processing order
   int32_t* counter;        // queue head (zeroed by the pre-pass)
   int64_t q_sb, q_sh, q_sl, k_sb, k_sh, k_sl, v_sb, v_sh, v_sl, o_sb, o_sh, o_sl;  // elements
-  int32_t H, L, M, N, nshift, QB, n_items, static_assign;
+  int32_t H, L, M, N, QB, n_items, static_assign;
+  // group -> key expansion without divisions: NT = keys per LDS tile of the launched variant
+  int32_t nt_div_n, nt_mod_n;
+  uint32_t n_recip16;   // ceil(65536 / N), used only when N < NT
   float c_log2;      // |scale| * log2(e): exp(scale*s) == exp2(c_log2 * s')
   float scale_abs;   // |scale|
   uint32_t q_sign;   // 0x80008000 if scale < 0 (the sign is moved onto Q, exactly), else 0

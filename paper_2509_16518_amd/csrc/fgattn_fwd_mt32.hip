@@ -1,15 +1,26 @@
-// Forward-kernel instantiations for the 32-row query tile (d = 64 and d = 128).
+// Forward-kernel instantiations for the 32-row query tile: d = 64 / 128; dense, one key per
+// group, N keys per group.
 #include "fgattn_fwd.hpp"
 #include "fgattn_launch.hpp"
 
 namespace fg {
 
+static_assert(FwdCfg<32, 128>::NT == (32 <= 32 ? 128 : 32 == 64 ? 64 : 32), "host-side NT table out of date");
+
+template <int D, int OCC>
+static int launch_d(const FwdArgs& a, int cus, hipStream_t stream, int* grid_only) {
+  static int occ[3][64];
+  constexpr int lds = FwdCfg<32, D>::LDS_BYTES;
+  if (a.indptr == nullptr)
+    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_DENSE, OCC>, lds, a, cus, stream, grid_only, occ[0]);
+  if (a.N == 1)
+    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_N1, OCC>, lds, a, cus, stream, grid_only, occ[1]);
+  return launch_variant(fgattn_fwd_kernel<32, D, NMODE_GROUPS, OCC>, lds, a, cus, stream, grid_only, occ[2]);
+}
+
 int launch_mt32(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only) {
-  static int occ64[64], occ128[64];
-  if (d == 64)
-    return launch_variant(fgattn_fwd_kernel<32, 64, 32, 2>, FwdCfg<32, 64, 32>::LDS_BYTES, a, cus, stream, grid_only, occ64);
-  return launch_variant(fgattn_fwd_kernel<32, 128, 32, 1>, FwdCfg<32, 128, 32>::LDS_BYTES, a, cus, stream, grid_only,
-                        occ128);
+  if (d == 64) return launch_d<64, 2>(a, cus, stream, grid_only);
+  return launch_d<128, 1>(a, cus, stream, grid_only);
 }
 
 }  // namespace fg

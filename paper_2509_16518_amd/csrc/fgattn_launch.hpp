@@ -22,6 +22,9 @@ int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipS
     occ_cache[dev] = occ;
   }
   long long want = (long long)cus * occ_cache[dev];
+#ifdef FG_ONE_WG_PER_CU
+  want = cus;
+#endif
   int grid = (int)(a.n_items < want ? a.n_items : want);
   if (grid < 1) grid = 1;
   if (grid_only) {
