@@ -48,9 +48,6 @@ __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0
 // the kernel orders these loads against LDS reads itself (vmcnt(0) + workgroup barrier once per
 // tile), which lets the gather of tile t+1 stay in flight during all of tile t's matrix work.
 __device__ __forceinline__ void gather16_to_lds(const void* base, unsigned byte_off, unsigned lds_base) {
-#ifdef FG_NODMA
-  return;
-#endif
   // base and lds_base are wave-uniform by construction; readfirstlane pins them to scalar registers
   // (it folds away when the value already lives in one)
   const uint64_t b64 = (uint64_t)(uintptr_t)base;
@@ -264,8 +261,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     auto tile_needs_check = [&](int t) { return short_group || (t + 1) * C::NT > total; };
     // full tiles with one key per group: one coalesced load per wave brings the RPW ids of its rows
     // (lane j holds the id of row j % RPW); a cross-lane permute hands each lane the id of its own row
-    auto scalar_ids = [&](int t) { return NMODE == NMODE_N1 && !tile_needs_check(t); };
-    auto fetch_ids_scalar = [&](int t) { widx = idx[t * C::NT + wv * C::RPW + (lane & (C::RPW - 1))]; };
+    auto coalesced_ids = [&](int t) { return NMODE == NMODE_N1 && !tile_needs_check(t); };
+    auto fetch_ids_coalesced = [&](int t) { widx = idx[t * C::NT + wv * C::RPW + (lane & (C::RPW - 1))]; };
     auto select_ids = [&]() {
 #pragma unroll
       for (int i = 0; i < C::IPW; i++) gi[i] = __builtin_amdgcn_ds_bpermute((i * C::RPI + lrow) << 2, widx);
@@ -330,48 +327,33 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     float l_run = 0.0f;        // this lane's partial sum of exponentials
 
     if (ntiles > 0) {
-      if (scalar_ids(0)) {
-        fetch_ids_scalar(0);
+      if (coalesced_ids(0)) {
+        fetch_ids_coalesced(0);
         select_ids();
       } else {
         fetch_ids_vector(0);
       }
       if (tile_needs_check(0)) issue_tile(0, 0, true); else issue_tile(0, 0, false);
       if (ntiles > 1) {
-        if (scalar_ids(1)) fetch_ids_scalar(1); else fetch_ids_vector(1);
+        if (coalesced_ids(1)) fetch_ids_coalesced(1); else fetch_ids_vector(1);
       }
     }
 
-#ifdef FG_TIMING
-    unsigned long long* dbg = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(a.counter) + 256 +
-                                                                    ((a.n_items * 4 + 255) / 256) * 256);
-    const bool tm = (blockIdx.x == FG_TIMING) && tid == 0 && iter == 1;
-#define FG_STAMP(k) if (tm && t < 160) dbg[t * 8 + (k)] = __builtin_amdgcn_s_memtime();
-#else
-#define FG_STAMP(k)
-#endif
     for (int t = 0; t < ntiles; t++) {
       const int stage = t & 1;
-      FG_STAMP(0)
-#ifndef FG_NOBARRIER
       wait_vmem_all();
       __syncthreads();
-#endif
       const unsigned char* kst = smem + stage * C::STAGE_BYTES;
       const unsigned char* vst = kst + C::TENSOR_BYTES;
-      FG_STAMP(1)
 
-      // ---- group ids: those of tile t+1 move into place, those of tile t+2 start their scalar fetch ----
+      // ---- group ids: those of tile t+1 move into place, those of tile t+2 start their fetch ----
       const bool has_next = t + 1 < ntiles;
       const bool next_checked = has_next && tile_needs_check(t + 1);
-      if (has_next && scalar_ids(t + 1)) select_ids();
-      if (t + 2 < ntiles && scalar_ids(t + 2)) fetch_ids_scalar(t + 2);
+      if (has_next && coalesced_ids(t + 1)) select_ids();
+      if (t + 2 < ntiles && coalesced_ids(t + 2)) fetch_ids_coalesced(t + 2);
 
       // ---- K fragments of this wave's 32 keys: the first half is read up front ----
       auto read_kf = [&](int s) {
-#ifdef FG_NOKVREAD
-        return qf[s];
-#endif
         return __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kst + krow + ((32 * s) ^ kxor)));
       };
       constexpr int KPRE = C::SSTEPS / 2;
@@ -380,20 +362,14 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       for (int s = 0; s < KPRE; s++) kf[s] = read_kf(s);
       __builtin_amdgcn_sched_barrier(0);
 
-      // a tile with padded or invalid positions (the last one) is gathered in one burst with range checks;
-      // full tiles are gathered one instruction per MFMA step below
-      if (next_checked) issue_tile(t + 1, stage ^ 1, true);
-      const bool spread = has_next && !next_checked;
-      constexpr int NDMA = 2 * C::IPW;
-      constexpr int DMA_PER_STEP = (NDMA + C::SSTEPS - 1) / C::SSTEPS;
-      constexpr int DMA_EVERY = NDMA >= C::SSTEPS ? 1 : C::SSTEPS / NDMA;
+      // ---- the gather of the next tile goes out while the K fragments arrive ----
+      if (has_next) {
+        if (next_checked) issue_tile(t + 1, stage ^ 1, true); else issue_tile(t + 1, stage ^ 1, false);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 
       // ---- S^T = K_rel Q^T; the first half of the V^T fragment reads rides behind the last MFMAs ----
       auto read_vf = [&](int db, int c, s16x4 (&dst)[2]) {
-#ifdef FG_NOKVREAD
-        dst[0] = s16x4{1, 2, 3, 4}; dst[1] = s16x4{1, 2, 3, 4};
-        return;
-#endif
         const unsigned char* p0 = vst + vrow + ((((4 * db) ^ vsw) + vlp) << 4) + (16 * c) * C::ROWB;
         dst[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS s16x4*)(p0));
         dst[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS s16x4*)(p0 + 8 * C::ROWB));
@@ -405,39 +381,17 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
 #pragma unroll
       for (int s = 0; s < C::SSTEPS; s++) {
         if (s + KPRE < C::SSTEPS) kf[s + KPRE] = read_kf(s + KPRE);   // second half, one read per MFMA
-#ifndef FG_NOQK
         S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], S, 0, 0, 0);
-#else
-        S[s] += kf[s][0] * qf[s][1];
-#endif
         if (s >= C::SSTEPS / 2) {   // kf[0 .. SSTEPS/2) are dead by now: their registers take these fragments
           const int j = s - C::SSTEPS / 2;
           read_vf(j / 2, j % 2, vf[j / 2][j % 2]);
         }
-        if (spread && s % DMA_EVERY == 0) {
-#pragma unroll
-          for (int e = 0; e < DMA_PER_STEP; e++) {
-            const int j = (s / DMA_EVERY) * DMA_PER_STEP + e;
-            if (j < NDMA) issue_one(j, t + 1, stage ^ 1, false);
-          }
-        }
       }
-      if (t + 2 < ntiles && !scalar_ids(t + 2)) fetch_ids_vector(t + 2);
+      if (t + 2 < ntiles && !coalesced_ids(t + 2)) fetch_ids_vector(t + 2);
       __builtin_amdgcn_sched_barrier(0);
-      FG_STAMP(2)
 
       // ---- online softmax: one query per lane; O is rescaled only when some lane's max moved ----
       bf16x8 P[2];
-#ifdef FG_NOSOFTMAX
-#pragma unroll
-      for (int c = 0; c < 2; c++) {
-        f32x8 f;
-#pragma unroll
-        for (int e = 0; e < 8; e++) f[e] = S[8 * c + e];
-        P[c] = __builtin_convertvector(f, bf16x8);
-      }
-      l_run += S[0];
-#else
       const bool masked = tile_needs_check(t);
       float m_new;
       if (masked) softmax_max<true>(S, bias + stage * C::NT + kw * 32, g, m_run, m_new);
@@ -453,10 +407,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       }
       if (masked) softmax_exp<true>(S, a.c_log2, m_run, l_run, P);
       else softmax_exp<false>(S, a.c_log2, m_run, l_run, P);
-#endif
       __builtin_amdgcn_sched_barrier(0);
-
-      FG_STAMP(3)
       // ---- O^T += V_rel^T P^T; the second half of the V^T fragments is read while the first half multiplies ----
 #pragma unroll
       for (int db = C::DBLK / 2; db < C::DBLK; db++)
@@ -467,16 +418,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
 #pragma unroll
         for (int c = 0; c < 2; c++) {
           s16x8 both = __builtin_shufflevector(vf[db][c][0], vf[db][c][1], 0, 1, 2, 3, 4, 5, 6, 7);
-#ifndef FG_NOPV
           O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), P[c], O[db], 0, 0, 0);
-#else
-          O[db][c] += (float)both[0] * (float)P[c][0];
-#endif
         }
-#ifdef FG_TIMING
-      if (tm && t < 160) { float keep = O[0][0] + O[1][1] + O[C::DBLK - 1][2]; asm volatile("" :: "v"(keep)); }
-#endif
-      FG_STAMP(4)
     }
 
     // ---------------- epilogue ----------------
