@@ -22,6 +22,9 @@ REPO = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, REPO)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+# HBM bytes per launch of the forward kernel on the wan-1.3b workload, from the FETCH_SIZE / WRITE_SIZE
+# rocprofv3 runs summarised in profiles/fgattn_fwd_kernel_wan-1.3b.md (scaled by the copy-kernel factors there)
+HBM_TRAFFIC_BYTES = {"wan-1.3b": 4.53e9}
 
 
 def log(msg):
@@ -138,7 +141,8 @@ def main():
         "dense_equiv_tflops": dense_flop / ms_step / 1e9,
         "gather_request_GBps": indices.size * w.N * 4.0 * w.d / ms_step / 1e6,
         "roofline": {"bound": "mfma", "achieved": useful / ms_main / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": useful / ms_main / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": useful / ms_main / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": HBM_TRAFFIC_BYTES.get(w.name),
                      "kernel": "fgattn_fwd_kernel", "kernel_ms": ms_main},
         "wall_s_timed_region": wall,
     }
