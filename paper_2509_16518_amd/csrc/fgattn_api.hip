@@ -233,7 +233,10 @@ static int run_forward(const void* q, const void* k, const void* v, const int64_
   a.n_items = (int32_t)n_items_of(p);
   a.static_assign = (p->flags & FGATTN_FLAG_STATIC_ASSIGN) ? 1 : 0;
   const float sabs = fabsf(p->scale);
+  // scale = 0 is run with a tiny positive exponent factor: valid keys still get p = exp2(tiny * s) = 1 exactly,
+  // while masked keys (score -inf) get exactly 0 instead of exp2(-inf * 0) = NaN
   a.c_log2 = sabs * 1.44269504088896340736f;
+  if (!(a.c_log2 > 1e-30f)) a.c_log2 = 1e-30f;
   a.scale_abs = sabs;
   a.q_sign = p->scale < 0.0f ? 0x80008000u : 0u;
   return launch_forward(a, p->d, dev.cus, stream, nullptr);

@@ -23,12 +23,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "fgattn_args.hpp"
 
 namespace fg {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) float f32x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -62,6 +66,35 @@ __device__ __forceinline__ void gather16_to_lds(const void* base, unsigned byte_
       : "v"(byte_off), "s"(base), "s"(lds_base)
       : "memory");   // m0 is a reserved register: no compiler-generated instruction of this kernel reads it
 }
+// The same transfer for a run of up to four 1 KiB loads that land back to back in LDS: M0 is written once
+// (gather16_first) and the following loads (gather16_next<K>) add K KiB through the instruction offset.  That
+// offset also enters the global address, so `base_m4k` is the true base minus 4096 and the byte offset carries
+// +4096 - 1024*K (kept non-negative: the 32-bit offset is zero-extended).
+__device__ __forceinline__ const void* pin_scalar(const void* p) {
+  // wave-uniform by construction; readfirstlane pins it to scalar registers (it folds away when already there)
+  const uint64_t b64 = (uint64_t)(uintptr_t)p;
+  return (const void*)(uintptr_t)(((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(b64 >> 32)) << 32) |
+                                  (unsigned)__builtin_amdgcn_readfirstlane((int)(b64 & 0xffffffffu)));
+}
+__device__ __forceinline__ void gather16_first(const void* base_m4k, unsigned byte_off, unsigned lds_base) {
+  base_m4k = pin_scalar(base_m4k);
+  lds_base = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_base);
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(byte_off), "s"(base_m4k), "s"(lds_base)
+      : "memory");
+}
+template <int K>
+__device__ __forceinline__ void gather16_next(const void* base_m4k, unsigned byte_off) {
+  static_assert(K >= 1 && K <= 3, "the instruction offset is 13-bit signed");
+  base_m4k = pin_scalar(base_m4k);
+  if (K == 1) asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" : : "v"(byte_off), "s"(base_m4k) : "memory");
+  if (K == 2) asm volatile("global_load_lds_dwordx4 %0, %1 offset:2048" : : "v"(byte_off), "s"(base_m4k) : "memory");
+  if (K == 3) asm volatile("global_load_lds_dwordx4 %0, %1 offset:3072" : : "v"(byte_off), "s"(base_m4k) : "memory");
+}
 __device__ __forceinline__ unsigned lds_address(const void* p) {
   return (unsigned)(uintptr_t)((FG_LDS const unsigned char*)p);
 }
@@ -75,6 +108,8 @@ __device__ __forceinline__ float lane_pair_sum(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+
+constexpr float kLazyLog2 = 8.0f;   // how far (log2 units) the exponent base may lag behind the running max
 
 template <int MT, int D>
 struct FwdCfg {
@@ -187,13 +222,16 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
   //   d =  64 (128-byte rows): kswz(r) = (r >> 1) & 7, vswz(r) = ((r >> 1) & 1) << 2
   // The gather writes LDS lane-linearly, so the swizzle is applied to the global source address: the lane
   // that lands on (row r, chunk pc) fetches logical chunk pc ^ swz(r).
-  // reader, K: byte offset of step s is krow + ((32*s) ^ kxor)
-  const int krow = (kw * 32 + ln) * C::ROWB;
-  const int kxor = (g ^ (D == 128 ? (ln & 15) : ((ln >> 1) & 7))) << 4;
+  // reader, K: byte offset of step s is kor ^ (32*s): the row base has its low 8 bits clear and the swizzle term
+  // ((g ^ kswz) << 4) only touches bits 4..7, so the sum folds into one XOR with the step constant
+  const int kor = ((kw * 32 + ln) * C::ROWB) | ((g ^ (D == 128 ? (ln & 15) : ((ln >> 1) & 7))) << 4);
   // reader, V: lane n = 4*kq + qq of 16-lane group (g,u) addresses key row 4g+kq, d offset 16u + 4qq
   const int vrow = (kw * 32 + 4 * g + kq) * C::ROWB + ((qq & 1) << 3);
   const int vlp = 2 * u + (qq >> 1);                                    // chunk within the 4-chunk d block
   const int vsw = D == 128 ? (kq << 2) : (((kq >> 1) & 1) << 2);        // vswz of this lane's rows
+  int voff[C::DBLK];                                                    // per-lane byte offset of d block db
+#pragma unroll
+  for (int db = 0; db < C::DBLK; db++) voff[db] = vrow + ((((4 * db) ^ vsw) + vlp) << 4);
   // loader: rows r0 + lrow with r0 a multiple of RPI; the lane-dependent part of the swizzled source chunk
   const unsigned kx = (unsigned)((pc ^ (D == 128 ? lrow : (lrow >> 1))) << 4);
   const unsigned vx = (unsigned)((pc ^ (D == 128 ? (lrow << 2) : (((lrow >> 1) & 1) << 2))) << 4);
@@ -251,29 +289,35 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     }
 
     // ---------------- loader ----------------
-    // Position p = t*NT + wv*RPW + i*RPI + lrow of the compacted list is fetched by this lane with load
-    // instruction i of tile t.  Group ids are fetched one tile ahead of the rows they address.
-    int gi[C::IPW];       // group id per load instruction, for the next tile to issue
+    // Position p = T*NT + wv*RPW + i*RPI + lrow of the compacted list is fetched by this lane with load
+    // instruction i of tile T.  Pipeline per tile T (one iteration per tile, one barrier each):
+    //   iteration T-3: group ids fetched          iteration T-2: ids -> key rows, K(T) gathered
+    //   iteration T-1: S(T) = K(T) Q^T, row max   iteration T  : exp -> P(T); V(T) gathered
+    //   iteration T+1: O += V(T)^T P(T)^T
+    // Past the end of the list the pipeline keeps running on the last tile again (clamped tile index): a few
+    // redundant, in-bounds gathers per work item instead of existence checks in every iteration.
+    int gi[C::IPW];       // group ids being fetched (next tile to convert)
     int wi[C::IPW];       // offset of the key inside its group (NMODE_GROUPS)
-    int widx = 0;         // lane j: id of row j % RPW of this wave's share of the next tile but one
-    int tq = 0, tr = 0;   // (t*NT) / N and (t*NT) % N for the next tile to prefetch, advanced without divisions
+    int widx = 0;         // coalesced id fetch: lane j holds the id of row j % RPW of this wave's rows
+    int keyA[C::IPW], keyB[C::IPW], keyC[C::IPW];   // key rows of tiles t, t+1, t+2 in iteration t
+    int tq = 0, tr = 0;   // (T*NT) / N and (T*NT) % N for the next tile to fetch ids for, advanced without divisions
     const int lpos = wv * C::RPW + lrow;
-    auto tile_needs_check = [&](int t) { return short_group || (t + 1) * C::NT > total; };
-    // full tiles with one key per group: one coalesced load per wave brings the RPW ids of its rows
-    // (lane j holds the id of row j % RPW); a cross-lane permute hands each lane the id of its own row
-    auto coalesced_ids = [&](int t) { return NMODE == NMODE_N1 && !tile_needs_check(t); };
-    auto fetch_ids_coalesced = [&](int t) { widx = idx[t * C::NT + wv * C::RPW + (lane & (C::RPW - 1))]; };
-    auto select_ids = [&]() {
-#pragma unroll
-      for (int i = 0; i < C::IPW; i++) gi[i] = __builtin_amdgcn_ds_bpermute((i * C::RPI + lrow) << 2, widx);
-    };
-    auto fetch_ids_vector = [&](int t) {
+    const int last = ntiles - 1;
+    auto tile_needs_check = [&](int T) { return short_group || (T + 1) * C::NT > total; };
+    // full tiles with one key per group: one coalesced load per wave brings the RPW ids of its rows;
+    // a cross-lane permute then hands each lane the id of its own row
+    auto coalesced_ids = [&](int T) { return NMODE == NMODE_N1 && !tile_needs_check(T); };
+    auto fetch_ids = [&](int T) {
       if (NMODE == NMODE_DENSE) return;
+      if (__builtin_expect(coalesced_ids(T), 1)) {
+        widx = idx[T * C::NT + wv * C::RPW + (lane & (C::RPW - 1))];
+        return;
+      }
 #pragma unroll
       for (int i = 0; i < C::IPW; i++) {
         int grp;
         if (NMODE == NMODE_N1) {
-          grp = t * C::NT + lpos + i * C::RPI;
+          grp = T * C::NT + lpos + i * C::RPI;
         } else {
           const int x = tr + lpos + i * C::RPI;          // < N + NT
           const int q = N >= C::NT ? (x >= N ? 1 : 0) : (int)(((unsigned)x * a.n_recip16) >> 16);
@@ -282,7 +326,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         }
         gi[i] = idx[min(grp, cnt - 1)];
       }
-      if (NMODE == NMODE_GROUPS) {
+      if (NMODE == NMODE_GROUPS && T < last) {   // a repeated (clamped) last tile must see the same tq, tr again
         tq += a.nt_div_n;
         tr += a.nt_mod_n;
         if (tr >= N) {
@@ -291,30 +335,56 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         }
       }
     };
-    // One of the 2*IPW gather instructions of tile t: j = 2*i + (0: K rows, 1: V rows).
-    // checked == false: every position of the tile is a real key (no bias writes, no range checks).
-    auto issue_one = [&](int j, int t, int stage, bool checked) {
-      const int i = j >> 1;
-      const unsigned kst = lds0 + stage * C::STAGE_BYTES;
-      const int r0 = wv * C::RPW + i * C::RPI;   // wave-uniform first row of this 1 KiB load
-      const int p = t * C::NT + lpos + i * C::RPI;
-      int key = NMODE == NMODE_DENSE ? p : NMODE == NMODE_N1 ? gi[i] : gi[i] * N + wi[i];
-      if (checked) {
-        const bool ok = p < total && key < a.L;
-        key = ok ? key : 0;
-        if ((j & 1) == 0 && pc == 0) bias[stage * C::NT + r0 + lrow] = ok ? 0.0f : -INFINITY;
+    // ids of tile T (fetched earlier) -> key rows in keyC; padded / out-of-range positions of a checked tile
+    // read row 0 and get a -inf score bias
+    auto make_keys = [&](int T) {
+      if (NMODE == NMODE_N1 && __builtin_expect(coalesced_ids(T), 1)) {
+#pragma unroll
+        for (int i = 0; i < C::IPW; i++) keyC[i] = __builtin_amdgcn_ds_bpermute((i * C::RPI + lrow) << 2, widx);
+        return;
       }
-      if ((j & 1) == 0) {
-        // uniform part of kswz(r0 + lrow): (r0 & 12) for d = 128, (r0 >> 1) & 4 for d = 64; vswz has none
-        const unsigned ku = (unsigned)((D == 128 ? (r0 & 12) : ((r0 >> 1) & 4)) << 4);
-        gather16_to_lds(kbase, __umul24((unsigned)key, k_rowb) + (kx ^ ku), kst + r0 * C::ROWB);
-      } else {
-        gather16_to_lds(vbase, __umul24((unsigned)key, v_rowb) + vx, kst + C::TENSOR_BYTES + r0 * C::ROWB);
+      const bool checked = tile_needs_check(T);
+#pragma unroll
+      for (int i = 0; i < C::IPW; i++) {
+        const int p = T * C::NT + lpos + i * C::RPI;
+        int key = NMODE == NMODE_DENSE ? p : NMODE == NMODE_N1 ? gi[i] : gi[i] * N + wi[i];
+        if (__builtin_expect(checked, 0)) {
+          const bool ok = p < total && key < a.L;
+          key = ok ? key : 0;
+          if (pc == 0) bias[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? 0.0f : -INFINITY;
+        }
+        keyC[i] = key;
       }
     };
-    auto issue_tile = [&](int t, int stage, bool checked) {
+    // LDS: K ring slots 0,1 then V ring slots 0,1, TENSOR_BYTES each.  A run of up to four gathers of one wave
+    // lands back to back, so only the first writes M0 and the others use the instruction offset (which also
+    // enters the global address: base - 4096 and a per-lane constant + 4096 - 1024*(i%4) compensate).
+    unsigned kcon[C::IPW], vcon[C::IPW];
 #pragma unroll
-      for (int j = 0; j < 2 * C::IPW; j++) issue_one(j, t, stage, checked);
+    for (int i = 0; i < C::IPW; i++) {
+      const int r0 = wv * C::RPW + i * C::RPI;
+      // uniform part of kswz(r0 + lrow): (r0 & 12) for d = 128, (r0 >> 1) & 4 for d = 64; vswz has none
+      const unsigned ku = (unsigned)((D == 128 ? (r0 & 12) : ((r0 >> 1) & 4)) << 4);
+      kcon[i] = (kx ^ ku) + 4096u - 1024u * (i & 3);
+      vcon[i] = vx + 4096u - 1024u * (i & 3);
+    }
+    const char* kbase_m4k = reinterpret_cast<const char*>(kbase) - 4096;
+    const char* vbase_m4k = reinterpret_cast<const char*>(vbase) - 4096;
+    auto gather_k = [&](auto ic, int slot, const int (&keys)[C::IPW]) {
+      constexpr int i = decltype(ic)::value;
+      const unsigned off = __umul24((unsigned)keys[i], k_rowb) + kcon[i];
+      if constexpr ((i & 3) == 0)
+        gather16_first(kbase_m4k, off, lds0 + slot * C::TENSOR_BYTES + (wv * C::RPW + i * C::RPI) * C::ROWB);
+      else
+        gather16_next<(i & 3)>(kbase_m4k, off);
+    };
+    auto gather_v = [&](auto ic, int slot, const int (&keys)[C::IPW]) {
+      constexpr int i = decltype(ic)::value;
+      const unsigned off = __umul24((unsigned)keys[i], v_rowb) + vcon[i];
+      if constexpr ((i & 3) == 0)
+        gather16_first(vbase_m4k, off, lds0 + (2 + slot) * C::TENSOR_BYTES + (wv * C::RPW + i * C::RPI) * C::ROWB);
+      else
+        gather16_next<(i & 3)>(vbase_m4k, off);
     };
 
     // ---------------- accumulators ----------------
@@ -323,103 +393,217 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     for (int db = 0; db < C::DBLK; db++)
 #pragma unroll
       for (int r = 0; r < 16; r++) O[db][r] = 0.0f;
-    float m_run = -INFINITY;   // running max of raw (unscaled) scores of this lane's query
+    f32x16 S;                  // S^T of the tile whose exponentials come next
+    bf16x8 PA[2], PB[2];       // P^T of even / odd tiles (one is multiplied with V while the other is produced)
+    float m_run = -INFINITY;   // exponent base (raw score units) of this lane's query; lags the true max lazily
     float l_run = 0.0f;        // this lane's partial sum of exponentials
+    float m_pend = -INFINITY;  // running max including the tile in S
+    bool resc = false;         // wave-uniform: the tile in S moves the exponent base (O, l must be rescaled)
 
-    if (ntiles > 0) {
-      if (coalesced_ids(0)) {
-        fetch_ids_coalesced(0);
-        select_ids();
-      } else {
-        fetch_ids_vector(0);
-      }
-      if (tile_needs_check(0)) issue_tile(0, 0, true); else issue_tile(0, 0, false);
-      if (ntiles > 1) {
-        if (coalesced_ids(1)) fetch_ids_coalesced(1); else fetch_ids_vector(1);
-      }
-    }
-
-    for (int t = 0; t < ntiles; t++) {
-      const int stage = t & 1;
-      wait_vmem_all();
-      __syncthreads();
-      const unsigned char* kst = smem + stage * C::STAGE_BYTES;
-      const unsigned char* vst = kst + C::TENSOR_BYTES;
-
-      // ---- group ids: those of tile t+1 move into place, those of tile t+2 start their fetch ----
-      const bool has_next = t + 1 < ntiles;
-      const bool next_checked = has_next && tile_needs_check(t + 1);
-      if (has_next && coalesced_ids(t + 1)) select_ids();
-      if (t + 2 < ntiles && coalesced_ids(t + 2)) fetch_ids_coalesced(t + 2);
-
-      // ---- K fragments of this wave's 32 keys: the first half is read up front ----
-      auto read_kf = [&](int s) {
-        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kst + krow + ((32 * s) ^ kxor)));
-      };
-      constexpr int KPRE = C::SSTEPS / 2;
-      bf16x8 kf[C::SSTEPS];
+    constexpr int NE = C::SSTEPS;          // MFMA slots per phase: PV slot e = (d block e/2, key half e%2); QK slot e = d chunk e
+    constexpr int AHEAD = 3;               // LDS fragment reads run this many slots ahead of their MFMA
+    constexpr int VPS = 16 / NE;           // score values handled per slot
+    // gathers per iteration and wave: IPW of V then IPW of K, spread over the NE slots of phase X
+    constexpr int NDMA = 2 * C::IPW;
+    constexpr int DMA_PER = (NDMA + NE - 1) / NE;
+    constexpr int DMA_EVERY = NDMA >= NE ? 1 : NE / NDMA;
+    auto read_vf = [&](const unsigned char* vst, int e) {
+      const int db = e >> 1, c = e & 1;
+      const unsigned char* p0 = vst + voff[db] + (16 * c) * C::ROWB;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS s16x4*)(p0));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS s16x4*)(p0 + 8 * C::ROWB));
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // O^T += V^T P^T with V in slot `vslot` (wave-uniform or a constant); with EXP, the exponentials of the tile
+    // in S run on the vector ALU between the MFMAs: P = exp2(c*(S - m)), row sum, bf16 pack into Pout.
+    auto pv_and_exp = [&](auto vslot, const bf16x8 (&Pin)[2], bf16x8 (&Pout)[2], auto with_exp) {
+      constexpr bool EXP = decltype(with_exp)::value;   // EXP also gathers V of the current tile into the other V slot
+      const unsigned char* vst = smem + (2 + vslot) * C::TENSOR_BYTES;
+      const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;   // a wave that has seen no valid key yet
+      const float neg_mc = -m_safe * a.c_log2;
+      float psum0 = 0.0f, psum1 = 0.0f;
+      bf16x8 vf[NE];
 #pragma unroll
-      for (int s = 0; s < KPRE; s++) kf[s] = read_kf(s);
-      __builtin_amdgcn_sched_barrier(0);
-
-      // ---- the gather of the next tile goes out while the K fragments arrive ----
-      if (has_next) {
-        if (next_checked) issue_tile(t + 1, stage ^ 1, true); else issue_tile(t + 1, stage ^ 1, false);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-
-      // ---- S^T = K_rel Q^T; the first half of the V^T fragment reads rides behind the last MFMAs ----
-      auto read_vf = [&](int db, int c, s16x4 (&dst)[2]) {
-        const unsigned char* p0 = vst + vrow + ((((4 * db) ^ vsw) + vlp) << 4) + (16 * c) * C::ROWB;
-        dst[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS s16x4*)(p0));
-        dst[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS s16x4*)(p0 + 8 * C::ROWB));
+      for (int e = 0; e < AHEAD; e++) vf[e] = read_vf(vst, e);
+      auto slot = [&](auto ec) {
+        constexpr int e = decltype(ec)::value;
+        if constexpr (e + AHEAD < NE) vf[e + AHEAD] = read_vf(vst, e + AHEAD);
+        O[e >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[e], Pin[e & 1], O[e >> 1], 0, 0, 0);
+        if constexpr (EXP) {
+          // V rows of the current tile (keys in keyA) -> the V slot this phase does not read, then K rows of the
+          // tile after next (keys in keyC) -> the K slot whose tile was multiplied during the previous iteration
+          if constexpr (e % DMA_EVERY == 0) {
+            constexpr int j0 = (e / DMA_EVERY) * DMA_PER;
+            if constexpr (j0 < C::IPW) gather_v(std::integral_constant<int, j0>(), 1 - vslot, keyA);
+            else if constexpr (j0 < NDMA) gather_k(std::integral_constant<int, j0 - C::IPW>(), 1 - vslot, keyC);
+            if constexpr (DMA_PER > 1) {
+              constexpr int j1 = j0 + 1;
+              if constexpr (j1 < C::IPW) gather_v(std::integral_constant<int, j1>(), 1 - vslot, keyA);
+              else if constexpr (j1 < NDMA) gather_k(std::integral_constant<int, j1 - C::IPW>(), 1 - vslot, keyC);
+            }
+          }
+#pragma unroll
+          for (int x = 0; x < VPS; x += 2) {
+            const int r = e * VPS + x;
+            // masked keys hold S = -inf and c_log2 > 0 (the host substitutes a tiny positive value for
+            // scale = 0), so their p is exactly 0 without a select
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[r], a.c_log2, neg_mc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[r + 1], a.c_log2, neg_mc));
+            psum0 += p0;
+            psum1 += p1;
+            f32x2 pp = {p0, p1};
+            bf16x2 pk = __builtin_convertvector(pp, bf16x2);
+            Pout[r >> 3][r & 7] = pk[0];
+            Pout[r >> 3][(r & 7) + 1] = pk[1];
+          }
+          __builtin_amdgcn_sched_barrier(0);   // keep one MFMA + its share of the exponentials per slot
+        }
       };
-      f32x16 S;
+      slot(std::integral_constant<int, 0>());
+      slot(std::integral_constant<int, 1>());
+      slot(std::integral_constant<int, 2>());
+      slot(std::integral_constant<int, 3>());
+      if constexpr (NE > 4) {
+        slot(std::integral_constant<int, 4>());
+        slot(std::integral_constant<int, 5>());
+        slot(std::integral_constant<int, 6>());
+        slot(std::integral_constant<int, 7>());
+      }
+      if (EXP) l_run += psum0 + psum1;
+    };
+    // S = K Q^T with K in slot `kslot`; then the row max of the new scores (tile Tm) and the rare decision to
+    // move the exponent base (see kLazyLog2).  Also rotates the key-row sets (t+1 -> t, t+2 -> t+1).
+    auto qk_and_max = [&](auto kslot, int Tm) {
+      const unsigned char* kst = smem + kslot * C::TENSOR_BYTES;
+      auto read_kf = [&](int s) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kst + (kor ^ (32 * s))));
+      };
+      bf16x8 kf[NE];
+#pragma unroll
+      for (int e = 0; e < AHEAD; e++) kf[e] = read_kf(e);
 #pragma unroll
       for (int r = 0; r < 16; r++) S[r] = 0.0f;
-      s16x4 vf[C::DBLK][2][2];
-#pragma unroll
-      for (int s = 0; s < C::SSTEPS; s++) {
-        if (s + KPRE < C::SSTEPS) kf[s + KPRE] = read_kf(s + KPRE);   // second half, one read per MFMA
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], S, 0, 0, 0);
-        if (s >= C::SSTEPS / 2) {   // kf[0 .. SSTEPS/2) are dead by now: their registers take these fragments
-          const int j = s - C::SSTEPS / 2;
-          read_vf(j / 2, j % 2, vf[j / 2][j % 2]);
-        }
+      auto slot = [&](auto ec) {
+        constexpr int e = decltype(ec)::value;
+        if constexpr (e + AHEAD < NE) kf[e + AHEAD] = read_kf(e + AHEAD);
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[e], qf[e], S, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      slot(std::integral_constant<int, 0>());
+      slot(std::integral_constant<int, 1>());
+      slot(std::integral_constant<int, 2>());
+      slot(std::integral_constant<int, 3>());
+      if constexpr (NE > 4) {
+        slot(std::integral_constant<int, 4>());
+        slot(std::integral_constant<int, 5>());
+        slot(std::integral_constant<int, 6>());
+        slot(std::integral_constant<int, 7>());
       }
-      if (t + 2 < ntiles && !coalesced_ids(t + 2)) fetch_ids_vector(t + 2);
-      __builtin_amdgcn_sched_barrier(0);
-
-      // ---- online softmax: one query per lane; O is rescaled only when some lane's max moved ----
-      bf16x8 P[2];
-      const bool masked = tile_needs_check(t);
+#pragma unroll
+      for (int i = 0; i < C::IPW; i++) {
+        keyA[i] = keyB[i];
+        keyB[i] = keyC[i];
+      }
       float m_new;
-      if (masked) softmax_max<true>(S, bias + stage * C::NT + kw * 32, g, m_run, m_new);
-      else softmax_max<false>(S, nullptr, g, m_run, m_new);
-      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-        const float alpha = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f((m_run - m_new) * a.c_log2);
+      if (__builtin_expect(tile_needs_check(Tm), 0))
+        softmax_max<true>(S, bias + (Tm & 1) * C::NT + kw * 32, g, m_pend, m_new);
+      else
+        softmax_max<false>(S, nullptr, g, m_pend, m_new);
+      m_pend = m_new;
+      const bool lane_moves = (m_run == -INFINITY) ? (m_new > m_run) : ((m_new - m_run) * a.c_log2 > kLazyLog2);
+      resc = __builtin_amdgcn_ballot_w64(lane_moves) != 0;
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    // Iteration t, PAR = t & 1 (a constant, so every LDS slot is an immediate):
+    //   X: P(t) = exp(S) on the vector ALU  ||  O += V(t-1)^T P(t-1)^T (V slot PAR^1)
+    //      ||  gathers V(t) -> V slot PAR and K(t+2) -> K slot PAR (each gather instruction holds the issuing wave
+    //          for the time its 1 KiB takes through the vector-memory path; the MFMAs run underneath)
+    //   Y: S = K(t+1) Q^T (K slot PAR^1), then the row max of tile t+1
+    // Every gathered tile thus has a full iteration to arrive before the barrier that publishes it.
+    auto iteration = [&](int t, auto parc, const bf16x8 (&Pin)[2], bf16x8 (&Pout)[2]) {
+      constexpr int PAR = decltype(parc)::value;
+      // K(t+1) and V(t-1), gathered during the previous iteration, become visible to every wave; every wave is
+      // done reading K(t) and V(t-2), whose slots this iteration refills
+      wait_vmem_all();
+      __syncthreads();
+      float alpha = 1.0f;
+      if (__builtin_expect(resc, 0)) {   // the exponent base moves: l now, O after the MFMAs of the old base
+        alpha = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f((m_run - m_pend) * a.c_log2);
         l_run *= alpha;
+        m_run = m_pend;
+      }
+      make_keys(min(t + 2, last));        // ids fetched during the previous iteration -> keyC
+      fetch_ids(min(t + 3, last));
+      pv_and_exp(std::integral_constant<int, PAR ^ 1>(), Pin, Pout, yes());
+      if (__builtin_expect(resc, 0)) {
 #pragma unroll
         for (int db = 0; db < C::DBLK; db++)
 #pragma unroll
           for (int r = 0; r < 16; r++) O[db][r] *= alpha;
-        m_run = m_new;
       }
-      if (masked) softmax_exp<true>(S, a.c_log2, m_run, l_run, P);
-      else softmax_exp<false>(S, a.c_log2, m_run, l_run, P);
-      __builtin_amdgcn_sched_barrier(0);
-      // ---- O^T += V_rel^T P^T; the second half of the V^T fragments is read while the first half multiplies ----
+      qk_and_max(std::integral_constant<int, PAR ^ 1>(), min(t + 1, last));
+    };
+
+    if (ntiles > 0) {
+      // prologue: K(0) -> K slot 0; V(0) -> V slot 1, only so that the first iteration's O += V^T P^T (with
+      // P = 0) multiplies finite numbers; then S(0) = K(0) Q^T while K(1) loads
 #pragma unroll
-      for (int db = C::DBLK / 2; db < C::DBLK; db++)
+      for (int c = 0; c < 2; c++)
 #pragma unroll
-        for (int c = 0; c < 2; c++) read_vf(db, c, vf[db][c]);
+        for (int e = 0; e < 8; e++) PB[c][e] = (__bf16)0.0f;
+      fetch_ids(0);
+      make_keys(0);
 #pragma unroll
-      for (int db = 0; db < C::DBLK; db++)
-#pragma unroll
-        for (int c = 0; c < 2; c++) {
-          s16x8 both = __builtin_shufflevector(vf[db][c][0], vf[db][c][1], 0, 1, 2, 3, 4, 5, 6, 7);
-          O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), P[c], O[db], 0, 0, 0);
-        }
+      for (int i = 0; i < C::IPW; i++) keyA[i] = keyB[i] = keyC[i];
+      auto burst = [&](auto ic) {
+        gather_k(ic, 0, keyC);
+      };
+      auto burst_v = [&](auto ic) {
+        gather_v(ic, 1, keyC);
+      };
+      burst(std::integral_constant<int, 0>());
+      if constexpr (C::IPW > 1) burst(std::integral_constant<int, 1>());
+      if constexpr (C::IPW > 2) { burst(std::integral_constant<int, 2>()); burst(std::integral_constant<int, 3>()); }
+      if constexpr (C::IPW > 4) {
+        burst(std::integral_constant<int, 4>()); burst(std::integral_constant<int, 5>());
+        burst(std::integral_constant<int, 6>()); burst(std::integral_constant<int, 7>());
+      }
+      burst_v(std::integral_constant<int, 0>());
+      if constexpr (C::IPW > 1) burst_v(std::integral_constant<int, 1>());
+      if constexpr (C::IPW > 2) { burst_v(std::integral_constant<int, 2>()); burst_v(std::integral_constant<int, 3>()); }
+      if constexpr (C::IPW > 4) {
+        burst_v(std::integral_constant<int, 4>()); burst_v(std::integral_constant<int, 5>());
+        burst_v(std::integral_constant<int, 6>()); burst_v(std::integral_constant<int, 7>());
+      }
+      fetch_ids(min(1, last));
+      wait_vmem_all();      // ids of tile 1
+      make_keys(min(1, last));
+      auto burst1 = [&](auto ic) { gather_k(ic, 1, keyC); };
+      burst1(std::integral_constant<int, 0>());
+      if constexpr (C::IPW > 1) burst1(std::integral_constant<int, 1>());
+      if constexpr (C::IPW > 2) { burst1(std::integral_constant<int, 2>()); burst1(std::integral_constant<int, 3>()); }
+      if constexpr (C::IPW > 4) {
+        burst1(std::integral_constant<int, 4>()); burst1(std::integral_constant<int, 5>());
+        burst1(std::integral_constant<int, 6>()); burst1(std::integral_constant<int, 7>());
+      }
+      fetch_ids(min(2, last));
+      wait_vmem_all();
+      __syncthreads();
+      // S(0) from K slot 0; keyA/keyB end up as keys(0)/keys(1)
+      qk_and_max(std::integral_constant<int, 0>(), 0);
+      m_run = m_pend;   // O = 0 and l = 0 so far: the first exponent base needs no rescale
+      resc = false;
+      int t = 0;
+      for (; t + 1 < ntiles; t += 2) {
+        iteration(t, std::integral_constant<int, 0>(), PB, PA);
+        iteration(t + 1, std::integral_constant<int, 1>(), PA, PB);
+      }
+      if (t < ntiles) iteration(t, std::integral_constant<int, 0>(), PB, PA);
+      wait_vmem_all();
+      __syncthreads();
+      if ((ntiles & 1) == 0) pv_and_exp((ntiles - 1) & 1, PB, PB, no());
+      else pv_and_exp((ntiles - 1) & 1, PA, PA, no());
     }
 
     // ---------------- epilogue ----------------
