@@ -157,35 +157,6 @@ __device__ __forceinline__ void softmax_max(f32x16& S, const float* bias_keys, i
   m_new = fmaxf(m_run, mx);
 }
 
-// Second half: p = exp2(c * (s - m)), partial row sum, P^T packed as the two B operands of the second MFMA.
-template <bool MASKED>
-__device__ __forceinline__ void softmax_exp(f32x16& S, float c_log2, float m_run, float& l_run, bf16x8 (&P)[2]) {
-  const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;
-  const float neg_mc = -m_safe * c_log2;
-  float psum0 = 0.0f, psum1 = 0.0f;
-#pragma unroll
-  for (int r = 0; r < 16; r += 2) {
-    float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[r], c_log2, neg_mc));
-    float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[r + 1], c_log2, neg_mc));
-    if (MASKED) {   // needed when c_log2 == 0: exp2(-inf * 0) is NaN, not 0
-      p0 = (S[r] == -INFINITY) ? 0.0f : p0;
-      p1 = (S[r + 1] == -INFINITY) ? 0.0f : p1;
-    }
-    S[r] = p0;
-    S[r + 1] = p1;
-    psum0 += p0;
-    psum1 += p1;
-  }
-  l_run += psum0 + psum1;
-#pragma unroll
-  for (int c = 0; c < 2; c++) {
-    f32x8 f;
-#pragma unroll
-    for (int e = 0; e < 8; e++) f[e] = S[8 * c + e];
-    P[c] = __builtin_convertvector(f, bf16x8);
-  }
-}
-
 // NMODE selects how a compacted key position maps to a key row:
 //   NMODE_DENSE   position == key (0% sparsity, no index list);
 //   NMODE_N1      one key per group: key = indices[position];
@@ -393,8 +364,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     for (int db = 0; db < C::DBLK; db++)
 #pragma unroll
       for (int r = 0; r < 16; r++) O[db][r] = 0.0f;
-    f32x16 S;                  // S^T of the tile whose exponentials come next
-    bf16x8 PA[2], PB[2];       // P^T of even / odd tiles (one is multiplied with V while the other is produced)
+    f32x16 SA, SB;             // S^T of even / odd tiles (one is turned into P while the other accumulates)
+    i32x4 PA[2], PB[2];        // P^T (packed bf16 pairs) of even / odd tiles: B operands of the second MFMA
     float m_run = -INFINITY;   // exponent base (raw score units) of this lane's query; lags the true max lazily
     float l_run = 0.0f;        // this lane's partial sum of exponentials
     float m_pend = -INFINITY;  // running max including the tile in S
@@ -414,24 +385,22 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS s16x4*)(p0 + 8 * C::ROWB));
       return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // O^T += V^T P^T with V in slot `vslot` (wave-uniform or a constant); with EXP, the exponentials of the tile
-    // in S run on the vector ALU between the MFMAs: P = exp2(c*(S - m)), row sum, bf16 pack into Pout.
-    auto pv_and_exp = [&](auto vslot, const bf16x8 (&Pin)[2], bf16x8 (&Pout)[2], auto with_exp) {
-      constexpr bool EXP = decltype(with_exp)::value;   // EXP also gathers V of the current tile into the other V slot
+    // O^T += V^T P^T with V in slot `vslot` (a constant).  With GATHER, the phase also issues this iteration's
+    // gathers, one per MFMA slot: V rows of the current tile (keys in keyA) -> the V slot this phase does not
+    // read, then K rows of the tile after next (keys in keyC) -> the K slot whose tile was multiplied during the
+    // previous iteration.
+    auto pv_phase = [&](auto vslot, const i32x4 (&Pin)[2], auto with_gather) {
+      constexpr bool GATHER = decltype(with_gather)::value;
       const unsigned char* vst = smem + (2 + vslot) * C::TENSOR_BYTES;
-      const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;   // a wave that has seen no valid key yet
-      const float neg_mc = -m_safe * a.c_log2;
-      float psum0 = 0.0f, psum1 = 0.0f;
+      const bf16x8 pin[2] = {__builtin_bit_cast(bf16x8, Pin[0]), __builtin_bit_cast(bf16x8, Pin[1])};
       bf16x8 vf[NE];
 #pragma unroll
       for (int e = 0; e < AHEAD; e++) vf[e] = read_vf(vst, e);
       auto slot = [&](auto ec) {
         constexpr int e = decltype(ec)::value;
         if constexpr (e + AHEAD < NE) vf[e + AHEAD] = read_vf(vst, e + AHEAD);
-        O[e >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[e], Pin[e & 1], O[e >> 1], 0, 0, 0);
-        if constexpr (EXP) {
-          // V rows of the current tile (keys in keyA) -> the V slot this phase does not read, then K rows of the
-          // tile after next (keys in keyC) -> the K slot whose tile was multiplied during the previous iteration
+        O[e >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[e], pin[e & 1], O[e >> 1], 0, 0, 0);
+        if constexpr (GATHER) {
           if constexpr (e % DMA_EVERY == 0) {
             constexpr int j0 = (e / DMA_EVERY) * DMA_PER;
             if constexpr (j0 < C::IPW) gather_v(std::integral_constant<int, j0>(), 1 - vslot, keyA);
@@ -442,21 +411,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
               else if constexpr (j1 < NDMA) gather_k(std::integral_constant<int, j1 - C::IPW>(), 1 - vslot, keyC);
             }
           }
-#pragma unroll
-          for (int x = 0; x < VPS; x += 2) {
-            const int r = e * VPS + x;
-            // masked keys hold S = -inf and c_log2 > 0 (the host substitutes a tiny positive value for
-            // scale = 0), so their p is exactly 0 without a select
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[r], a.c_log2, neg_mc));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[r + 1], a.c_log2, neg_mc));
-            psum0 += p0;
-            psum1 += p1;
-            f32x2 pp = {p0, p1};
-            bf16x2 pk = __builtin_convertvector(pp, bf16x2);
-            Pout[r >> 3][r & 7] = pk[0];
-            Pout[r >> 3][(r & 7) + 1] = pk[1];
-          }
-          __builtin_amdgcn_sched_barrier(0);   // keep one MFMA + its share of the exponentials per slot
+          __builtin_amdgcn_sched_barrier(0);
         }
       };
       slot(std::integral_constant<int, 0>());
@@ -469,25 +424,48 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         slot(std::integral_constant<int, 6>());
         slot(std::integral_constant<int, 7>());
       }
-      if (EXP) l_run += psum0 + psum1;
     };
-    // S = K Q^T with K in slot `kslot`; then the row max of the new scores (tile Tm) and the rare decision to
-    // move the exponent base (see kLazyLog2).  Also rotates the key-row sets (t+1 -> t, t+2 -> t+1).
-    auto qk_and_max = [&](auto kslot, int Tm) {
+    // Sn = K Q^T with K in slot `kslot` (tile Tm).  With EXP, the exponentials of the previous tile's scores So
+    // run on the vector ALU in the shadow of the dependent MFMA chain: P = exp2(c*(So - m)), row sum, bf16 pack
+    // into Pout.  Then the row max of the new scores and the rare decision to move the exponent base (see
+    // kLazyLog2).  Also rotates the key-row sets (t+1 -> t, t+2 -> t+1).
+    auto qk_phase = [&](auto kslot, int Tm, f32x16& Sn, const f32x16& So, i32x4 (&Pout)[2], auto with_exp) {
+      constexpr bool EXP = decltype(with_exp)::value;
       const unsigned char* kst = smem + kslot * C::TENSOR_BYTES;
       auto read_kf = [&](int s) {
         return __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kst + (kor ^ (32 * s))));
       };
+      const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;   // a wave that has seen no valid key yet
+      const float neg_mc = -m_safe * a.c_log2;
+      float psum0 = 0.0f, psum1 = 0.0f;
       bf16x8 kf[NE];
 #pragma unroll
       for (int e = 0; e < AHEAD; e++) kf[e] = read_kf(e);
 #pragma unroll
-      for (int r = 0; r < 16; r++) S[r] = 0.0f;
+      for (int r = 0; r < 16; r++) Sn[r] = 0.0f;
       auto slot = [&](auto ec) {
         constexpr int e = decltype(ec)::value;
         if constexpr (e + AHEAD < NE) kf[e + AHEAD] = read_kf(e + AHEAD);
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[e], qf[e], S, 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[e], qf[e], Sn, 0, 0, 0);
+        if constexpr (EXP) {
+#pragma unroll
+          for (int x = 0; x < VPS; x += 2) {
+            const int r = e * VPS + x;
+            // masked keys hold S = -inf and c_log2 > 0 (the host substitutes a tiny positive value for
+            // scale = 0), so their p is exactly 0 without a select
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(So[r], a.c_log2, neg_mc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(So[r + 1], a.c_log2, neg_mc));
+            psum0 += p0;
+            psum1 += p1;
+            f32x2 pp = {p0, p1};
+            int pk = __builtin_bit_cast(int, __builtin_convertvector(pp, bf16x2));
+            // the packed pair is consumed only after the next barrier; without this pin the compiler sinks the
+            // whole exponential block out of the MFMA shadow to the end of the phase
+            asm volatile("" : "+v"(pk));
+            Pout[r >> 3][(r & 7) >> 1] = pk;
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep one MFMA + its share of the exponentials per slot
       };
       slot(std::integral_constant<int, 0>());
       slot(std::integral_constant<int, 1>());
@@ -499,6 +477,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         slot(std::integral_constant<int, 6>());
         slot(std::integral_constant<int, 7>());
       }
+      if (EXP) l_run += psum0 + psum1;
 #pragma unroll
       for (int i = 0; i < C::IPW; i++) {
         keyA[i] = keyB[i];
@@ -506,9 +485,9 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       }
       float m_new;
       if (__builtin_expect(tile_needs_check(Tm), 0))
-        softmax_max<true>(S, bias + (Tm & 1) * C::NT + kw * 32, g, m_pend, m_new);
+        softmax_max<true>(Sn, bias + (Tm & 1) * C::NT + kw * 32, g, m_pend, m_new);
       else
-        softmax_max<false>(S, nullptr, g, m_pend, m_new);
+        softmax_max<false>(Sn, nullptr, g, m_pend, m_new);
       m_pend = m_new;
       const bool lane_moves = (m_run == -INFINITY) ? (m_new > m_run) : ((m_new - m_run) * a.c_log2 > kLazyLog2);
       resc = __builtin_amdgcn_ballot_w64(lane_moves) != 0;
@@ -516,12 +495,12 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
     // Iteration t, PAR = t & 1 (a constant, so every LDS slot is an immediate):
-    //   X: P(t) = exp(S) on the vector ALU  ||  O += V(t-1)^T P(t-1)^T (V slot PAR^1)
-    //      ||  gathers V(t) -> V slot PAR and K(t+2) -> K slot PAR (each gather instruction holds the issuing wave
-    //          for the time its 1 KiB takes through the vector-memory path; the MFMAs run underneath)
-    //   Y: S = K(t+1) Q^T (K slot PAR^1), then the row max of tile t+1
+    //   X: O += V(t-1)^T P(t-1)^T (V slot PAR^1)  ||  gathers V(t) -> V slot PAR and K(t+2) -> K slot PAR (each
+    //      gather instruction holds the issuing wave for the time its 1 KiB takes through the vector-memory path;
+    //      the MFMAs run underneath)
+    //   Y: S(t+1) = K(t+1) Q^T (K slot PAR^1)  ||  P(t) = exp(S(t)) on the vector ALU; then the row max of S(t+1)
     // Every gathered tile thus has a full iteration to arrive before the barrier that publishes it.
-    auto iteration = [&](int t, auto parc, const bf16x8 (&Pin)[2], bf16x8 (&Pout)[2]) {
+    auto iteration = [&](int t, auto parc, const i32x4 (&Pin)[2], i32x4 (&Pout)[2], f32x16& Sn, const f32x16& So) {
       constexpr int PAR = decltype(parc)::value;
       // K(t+1) and V(t-1), gathered during the previous iteration, become visible to every wave; every wave is
       // done reading K(t) and V(t-2), whose slots this iteration refills
@@ -535,14 +514,14 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       }
       make_keys(min(t + 2, last));        // ids fetched during the previous iteration -> keyC
       fetch_ids(min(t + 3, last));
-      pv_and_exp(std::integral_constant<int, PAR ^ 1>(), Pin, Pout, yes());
+      pv_phase(std::integral_constant<int, PAR ^ 1>(), Pin, yes());
       if (__builtin_expect(resc, 0)) {
 #pragma unroll
         for (int db = 0; db < C::DBLK; db++)
 #pragma unroll
           for (int r = 0; r < 16; r++) O[db][r] *= alpha;
       }
-      qk_and_max(std::integral_constant<int, PAR ^ 1>(), min(t + 1, last));
+      qk_phase(std::integral_constant<int, PAR ^ 1>(), min(t + 1, last), Sn, So, Pout, yes());
     };
 
     if (ntiles > 0) {
@@ -551,7 +530,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
 #pragma unroll
       for (int c = 0; c < 2; c++)
 #pragma unroll
-        for (int e = 0; e < 8; e++) PB[c][e] = (__bf16)0.0f;
+        for (int e = 0; e < 4; e++) PB[c][e] = 0;
       fetch_ids(0);
       make_keys(0);
 #pragma unroll
@@ -591,19 +570,19 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       wait_vmem_all();
       __syncthreads();
       // S(0) from K slot 0; keyA/keyB end up as keys(0)/keys(1)
-      qk_and_max(std::integral_constant<int, 0>(), 0);
+      qk_phase(std::integral_constant<int, 0>(), 0, SA, SA, PA, no());
       m_run = m_pend;   // O = 0 and l = 0 so far: the first exponent base needs no rescale
       resc = false;
       int t = 0;
       for (; t + 1 < ntiles; t += 2) {
-        iteration(t, std::integral_constant<int, 0>(), PB, PA);
-        iteration(t + 1, std::integral_constant<int, 1>(), PA, PB);
+        iteration(t, std::integral_constant<int, 0>(), PB, PA, SB, SA);
+        iteration(t + 1, std::integral_constant<int, 1>(), PA, PB, SA, SB);
       }
-      if (t < ntiles) iteration(t, std::integral_constant<int, 0>(), PB, PA);
+      if (t < ntiles) iteration(t, std::integral_constant<int, 0>(), PB, PA, SB, SA);
       wait_vmem_all();
       __syncthreads();
-      if ((ntiles & 1) == 0) pv_and_exp((ntiles - 1) & 1, PB, PB, no());
-      else pv_and_exp((ntiles - 1) & 1, PA, PA, no());
+      if ((ntiles & 1) == 0) pv_phase(std::integral_constant<int, 1>(), PB, no());
+      else pv_phase(std::integral_constant<int, 0>(), PA, no());
     }
 
     // ---------------- epilogue ----------------
