@@ -24,7 +24,7 @@ sys.path.insert(0, REPO)
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 # HBM bytes per launch of the forward kernel on the wan-1.3b workload, from the FETCH_SIZE / WRITE_SIZE
 # rocprofv3 runs summarised in profiles/fgattn_fwd_kernel_wan-1.3b.md (scaled by the copy-kernel factors there)
-HBM_TRAFFIC_BYTES = {"wan-1.3b": 4.53e9}
+HBM_TRAFFIC_BYTES = {"wan-1.3b": 5.58e9}
 
 
 def log(msg):
@@ -146,6 +146,22 @@ def main():
                      "kernel": "fgattn_fwd_kernel", "kernel_ms": ms_main},
         "wall_s_timed_region": wall,
     }
+    if w.M == 64 and w.d == 128 and w.N == 1:
+        # the two halves of the forward kernel timed apart on the same launch shape (results discarded)
+        scratch_out = torch.empty_like(dq)
+        scratch_lse = torch.empty_like(lse)
+
+        def part(which):
+            return lambda: F.fgattn_forward_part(dq, dk, dv, d_indptr, d_indices, p_reuse, scratch_out, scratch_lse,
+                                                 ws, which)
+        ms_gather = time_calls(part(F.PART_GATHER), 2, max(3, args.steps // 2))
+        ms_compute = time_calls(part(F.PART_COMPUTE), 2, max(3, args.steps // 2))
+        gather_bytes = indices.size * w.N * 4.0 * w.d
+        res["parts"] = {"gather_only_ms": ms_gather, "compute_only_ms": ms_compute,
+                        "gather_only_TBps": gather_bytes / ms_gather / 1e9,
+                        "gather_TBps_in_full_kernel": gather_bytes / ms_main / 1e9,
+                        "compute_only_pct_bf16_mfma_peak": 100.0 * useful / ms_compute / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+        del scratch_out, scratch_lse
     if not args.no_dense:
         def dense_step():
             F.fgattn_dense_forward(dq, dk, dv, p, out, lse, ws)

@@ -90,6 +90,18 @@ int fgattn_forward(const void* q, const void* k, const void* v, const int64_t* m
 int fgattn_dense_forward(const void* q, const void* k, const void* v, const fgattn_params* p, void* out, float* lse,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement aid, not part of the method: runs one half of fgattn_forward's kernel on the same launch shape,
+ * FGATTN_PART_GATHER = index translation and K/V row gathers only (the data movement of Sec. 4.1),
+ * FGATTN_PART_COMPUTE = everything except the row gathers (MFMA, softmax, LDS reads on whatever the tiles hold).
+ * Same arguments and error behaviour as fgattn_forward; only M = 64, d = 128, N = 1 is built (else
+ * FGATTN_E_SHAPE; an unknown `part` gives FGATTN_E_FLAGS).  `out` and `lse` are overwritten with meaningless
+ * values. */
+#define FGATTN_PART_GATHER 1
+#define FGATTN_PART_COMPUTE 2
+int fgattn_forward_part(const void* q, const void* k, const void* v, const int64_t* mask_indptr,
+                        const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* workspace,
+                        size_t workspace_bytes, int part, void* stream);
+
 /* Only the ordering pre-pass of fgattn_forward (Appendix B: cost of an item = length of its
  * key/value list; longest first): fills `workspace`.  A later fgattn_forward with
  * FGATTN_FLAG_REUSE_PLAN and the same mask/params skips it. */

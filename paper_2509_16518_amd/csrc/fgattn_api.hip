@@ -192,7 +192,7 @@ static int run_plan(const int64_t* indptr, const fgattn_params* p, void* workspa
 
 static int run_forward(const void* q, const void* k, const void* v, const int64_t* indptr, const int32_t* indices,
                        const fgattn_params* p, void* out, float* lse, void* workspace, size_t workspace_bytes,
-                       void* stream_v) {
+                       void* stream_v, int part = 0) {
   int rc = check_shape(p);
   if (rc) return rc;
   rc = check_tensors(q, k, v, out, lse, p);
@@ -239,6 +239,7 @@ static int run_forward(const void* q, const void* k, const void* v, const int64_
   if (!(a.c_log2 > 1e-30f)) a.c_log2 = 1e-30f;
   a.scale_abs = sabs;
   a.q_sign = p->scale < 0.0f ? 0x80008000u : 0u;
+  if (part != 0) return launch_part(a, part, dev.cus, stream);
   return launch_forward(a, p->d, dev.cus, stream, nullptr);
 }
 
@@ -261,6 +262,15 @@ int fgattn_forward(const void* q, const void* k, const void* v, const int64_t* m
 int fgattn_dense_forward(const void* q, const void* k, const void* v, const fgattn_params* p, void* out, float* lse,
                          void* workspace, size_t workspace_bytes, void* stream) {
   return fg::run_forward(q, k, v, nullptr, nullptr, p, out, lse, workspace, workspace_bytes, stream);
+}
+
+int fgattn_forward_part(const void* q, const void* k, const void* v, const int64_t* mask_indptr,
+                        const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* workspace,
+                        size_t workspace_bytes, int part, void* stream) {
+  if (!mask_indptr || !mask_indices) return FGATTN_E_NULL;
+  if (part != FGATTN_PART_GATHER && part != FGATTN_PART_COMPUTE) return FGATTN_E_FLAGS;
+  if (p && (p->M != 64 || p->d != 128 || p->N != 1)) return FGATTN_E_SHAPE;
+  return fg::run_forward(q, k, v, mask_indptr, mask_indices, p, out, lse, workspace, workspace_bytes, stream, part);
 }
 
 int fgattn_plan(const int64_t* mask_indptr, const fgattn_params* p, void* workspace, size_t workspace_bytes,

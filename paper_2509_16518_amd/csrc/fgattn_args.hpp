@@ -30,6 +30,9 @@ struct FwdArgs {
 // size is stored there.  Returns an FGATTN_* code.
 int launch_forward(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only);
 
+// Gather-only (part = 1) or compute-only (part = 2) instantiation of the M = 64, d = 128, N = 1 variant.
+int launch_part(const FwdArgs& a, int part, int cus, hipStream_t stream);
+
 // One translation unit per query-tile size keeps compile times parallel.
 int launch_mt32(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only);
 int launch_mt64(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only);

@@ -163,7 +163,12 @@ __device__ __forceinline__ void softmax_max(f32x16& S, const float* bias_keys, i
 //   NMODE_GROUPS  N >= 1 keys per group: key = indices[position / N] * N + position % N.
 enum { NMODE_DENSE = 0, NMODE_N1 = 1, NMODE_GROUPS = 2 };
 
-template <int MT, int D, int NMODE, int OCC>
+// PART selects what is executed: PART_ALL is the forward pass; PART_GATHER keeps only the index translation and
+// the row gathers, PART_COMPUTE everything but the row gathers (both leave meaningless results and exist so that
+// the two halves of the kernel can be timed apart on the same launch shape).
+enum { PART_ALL = 0, PART_GATHER = 1, PART_COMPUTE = 2 };
+
+template <int MT, int D, int NMODE, int OCC, int PART = PART_ALL>
 __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
   using C = FwdCfg<MT, D>;
   constexpr bool DENSE = NMODE == NMODE_DENSE;
@@ -343,6 +348,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     const char* vbase_m4k = reinterpret_cast<const char*>(vbase) - 4096;
     auto gather_k = [&](auto ic, int slot, const int (&keys)[C::IPW]) {
       constexpr int i = decltype(ic)::value;
+      if constexpr (PART == PART_COMPUTE) return;
       const unsigned off = __umul24((unsigned)keys[i], k_rowb) + kcon[i];
       if constexpr ((i & 3) == 0)
         gather16_first(kbase_m4k, off, lds0 + slot * C::TENSOR_BYTES + (wv * C::RPW + i * C::RPI) * C::ROWB);
@@ -351,6 +357,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     };
     auto gather_v = [&](auto ic, int slot, const int (&keys)[C::IPW]) {
       constexpr int i = decltype(ic)::value;
+      if constexpr (PART == PART_COMPUTE) return;
       const unsigned off = __umul24((unsigned)keys[i], v_rowb) + vcon[i];
       if constexpr ((i & 3) == 0)
         gather16_first(vbase_m4k, off, lds0 + (2 + slot) * C::TENSOR_BYTES + (wv * C::RPW + i * C::RPI) * C::ROWB);
@@ -395,11 +402,14 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       const bf16x8 pin[2] = {__builtin_bit_cast(bf16x8, Pin[0]), __builtin_bit_cast(bf16x8, Pin[1])};
       bf16x8 vf[NE];
 #pragma unroll
-      for (int e = 0; e < AHEAD; e++) vf[e] = read_vf(vst, e);
+      for (int e = 0; e < AHEAD; e++)
+        if constexpr (PART != PART_GATHER) vf[e] = read_vf(vst, e);
       auto slot = [&](auto ec) {
         constexpr int e = decltype(ec)::value;
-        if constexpr (e + AHEAD < NE) vf[e + AHEAD] = read_vf(vst, e + AHEAD);
-        O[e >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[e], pin[e & 1], O[e >> 1], 0, 0, 0);
+        if constexpr (PART != PART_GATHER) {
+          if constexpr (e + AHEAD < NE) vf[e + AHEAD] = read_vf(vst, e + AHEAD);
+          O[e >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[e], pin[e & 1], O[e >> 1], 0, 0, 0);
+        }
         if constexpr (GATHER) {
           if constexpr (e % DMA_EVERY == 0) {
             constexpr int j0 = (e / DMA_EVERY) * DMA_PER;
@@ -431,6 +441,14 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     // kLazyLog2).  Also rotates the key-row sets (t+1 -> t, t+2 -> t+1).
     auto qk_phase = [&](auto kslot, int Tm, f32x16& Sn, const f32x16& So, i32x4 (&Pout)[2], auto with_exp) {
       constexpr bool EXP = decltype(with_exp)::value;
+      if constexpr (PART == PART_GATHER) {   // only the bookkeeping the gathers depend on
+#pragma unroll
+        for (int i = 0; i < C::IPW; i++) {
+          keyA[i] = keyB[i];
+          keyB[i] = keyC[i];
+        }
+        return;
+      }
       const unsigned char* kst = smem + kslot * C::TENSOR_BYTES;
       auto read_kf = [&](int s) {
         return __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kst + (kor ^ (32 * s))));

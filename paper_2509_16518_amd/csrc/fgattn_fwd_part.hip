@@ -1,0 +1,17 @@
+// Partial instantiations of the forward kernel (gather only / compute only) for the variant the headline
+// workload runs (64-row query tile, d = 128, one key per group): they let a benchmark time the two halves of
+// the kernel apart on the launch shape of the full kernel.
+#include "fgattn_fwd.hpp"
+#include "fgattn_launch.hpp"
+
+namespace fg {
+
+int launch_part(const FwdArgs& a, int part, int cus, hipStream_t stream) {
+  static int occ[2][64];
+  constexpr int lds = FwdCfg<64, 128>::LDS_BYTES;
+  if (part == PART_GATHER)
+    return launch_variant(fgattn_fwd_kernel<64, 128, NMODE_N1, 2, PART_GATHER>, lds, a, cus, stream, nullptr, occ[0]);
+  return launch_variant(fgattn_fwd_kernel<64, 128, NMODE_N1, 2, PART_COMPUTE>, lds, a, cus, stream, nullptr, occ[1]);
+}
+
+}  // namespace fg

@@ -45,6 +45,8 @@ def lib():
         L.fgattn_workspace_bytes.restype = ctypes.c_size_t
         L.fgattn_forward.argtypes = [vp, vp, vp, i64p, vp, pp, vp, vp, vp, ctypes.c_size_t, vp]
         L.fgattn_forward.restype = ctypes.c_int
+        L.fgattn_forward_part.argtypes = [vp, vp, vp, i64p, vp, pp, vp, vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
+        L.fgattn_forward_part.restype = ctypes.c_int
         L.fgattn_dense_forward.argtypes = [vp, vp, vp, pp, vp, vp, vp, ctypes.c_size_t, vp]
         L.fgattn_dense_forward.restype = ctypes.c_int
         L.fgattn_plan.argtypes = [i64p, pp, vp, ctypes.c_size_t, vp]
@@ -96,6 +98,17 @@ def fgattn_forward(q, k, v, mask_indptr, mask_indices, params, out, lse, workspa
                                 mask_indices.data_ptr(), ctypes.byref(params), out.data_ptr(), lse.data_ptr(),
                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                 _stream_ptr(stream)))
+
+
+PART_GATHER, PART_COMPUTE = 1, 2
+
+
+def fgattn_forward_part(q, k, v, mask_indptr, mask_indices, params, out, lse, workspace, part, stream=None):
+    """Measurement aid: one half of the forward kernel (results in out / lse are meaningless)."""
+    _check(lib().fgattn_forward_part(q.data_ptr(), k.data_ptr(), v.data_ptr(), mask_indptr.data_ptr(),
+                                     mask_indices.data_ptr(), ctypes.byref(params), out.data_ptr(), lse.data_ptr(),
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(part),
+                                     _stream_ptr(stream)))
 
 
 def fgattn_dense_forward(q, k, v, params, out, lse, workspace, stream=None):
