@@ -5,7 +5,8 @@ paper's problem statement (Sec. 2; Sec. 4.1; Fig. 1b).  It shares no code with t
 path and is imported only by tests, the smoke check and the benchmark's CPU-baseline leg.
 
 `attention(...)` evaluates chosen work items with the C implementation in
-fgattn_oracle.c (built with gcc on first use).
+fgattn_oracle.c (built with gcc on first use).  `pool(...)` and `topp_rows(...)` are the
+mean-query/key top-p mask of Sec. 4.3 (fgmask_oracle.c).
 """
 import ctypes
 import os
@@ -15,7 +16,9 @@ import numpy as np
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(_DIR, "libfgattn_oracle.so")
+MASK_LIB = os.path.join(_DIR, "libfgmask_oracle.so")
 _lib = None
+_mask_lib = None
 
 
 def build(force=True):
@@ -26,6 +29,12 @@ def build(force=True):
         r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         if r.returncode != 0:
             raise RuntimeError("oracle build failed:\n" + r.stdout)
+    if force or not os.path.exists(MASK_LIB):
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared", os.path.join(_DIR, "fgmask_oracle.c"),
+               "-o", MASK_LIB, "-lm"]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("mask oracle build failed:\n" + r.stdout)
     return LIB
 
 
@@ -76,3 +85,71 @@ def attention(q_bits, k_bits, v_bits, M, N, scale, indptr, indices, items=None):
     if rc != 0:
         raise ValueError("oracle rejected its input (group id or item id out of range)")
     return out, lse
+
+
+def _load_mask():
+    global _mask_lib
+    if _mask_lib is None:
+        if not os.path.exists(MASK_LIB):
+            build()
+        lib = ctypes.CDLL(MASK_LIB)
+        lib.fgmask_oracle_pool.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.c_void_p]
+        lib.fgmask_oracle_pool.restype = None
+        lib.fgmask_oracle_row.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
+                                          ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p]
+        lib.fgmask_oracle_row.restype = ctypes.c_int32
+        _mask_lib = lib
+    return _mask_lib
+
+
+def pool(x_bits, rows_per_block):
+    """Block means of Sec. 4.3 as bf16 bits: x [..., L, d] -> [slices, ceil(L/rows_per_block), d]."""
+    x = np.ascontiguousarray(x_bits, dtype=np.uint16)
+    L, d = x.shape[-2], x.shape[-1]
+    slices = x.size // (L * d)
+    nb = (L + rows_per_block - 1) // rows_per_block
+    out = np.empty((slices, nb, d), dtype=np.uint16)
+    _load_mask().fgmask_oracle_pool(x.ctypes.data, slices, L, d, int(rows_per_block), out.ctypes.data)
+    return out
+
+
+def topp_rows(q_bits, k_bits, M, N, scale, p, rows=None):
+    """Top-p selection of Sec. 4.3 for the given work items (w = slice*ceil(L/M) + i; default all).
+
+    Returns a list of (kept, order, cum) per requested item: `order` ranks all key blocks of the
+    item's slice (most probable first, ties by ascending id), `cum` is the cumulative probability
+    along it, and the mask keeps order[:kept].
+    """
+    qp = pool(q_bits, M)
+    kp = pool(k_bits, N)
+    slices, QB, d = qp.shape
+    G = kp.shape[1]
+    if rows is None:
+        rows = range(slices * QB)
+    lib = _load_mask()
+    res = []
+    for w in rows:
+        s, i = divmod(int(w), QB)
+        order = np.empty(G, dtype=np.int32)
+        cum = np.empty(G, dtype=np.float64)
+        qa = np.ascontiguousarray(qp[s, i])
+        ka = np.ascontiguousarray(kp[s])
+        kept = lib.fgmask_oracle_row(qa.ctypes.data, ka.ctypes.data, G, d, float(scale), float(p), order.ctypes.data,
+                                     cum.ctypes.data)
+        if kept < 0:
+            raise MemoryError("mask oracle allocation failed")
+        res.append((int(kept), order, cum))
+    return res
+
+
+def topp_csr(q_bits, k_bits, M, N, scale, p):
+    """The whole mask as CSR (ascending key-block ids per item): (indptr int64, indices int32)."""
+    rows = topp_rows(q_bits, k_bits, M, N, scale, p)
+    indptr = np.zeros(len(rows) + 1, dtype=np.int64)
+    parts = []
+    for n, (kept, order, _) in enumerate(rows):
+        parts.append(np.sort(order[:kept]))
+        indptr[n + 1] = indptr[n] + kept
+    indices = np.concatenate(parts).astype(np.int32) if parts else np.zeros(0, dtype=np.int32)
+    return indptr, indices
