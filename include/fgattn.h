@@ -114,6 +114,30 @@ int fgattn_plan(const int64_t* mask_indptr, const fgattn_params* p, void* worksp
 int fgattn_validate_mask(const int64_t* mask_indptr, const int32_t* mask_indices, const fgattn_params* p,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Mean-query/key top-p mask (paper Sec. 4.3): builds, on the device, the CSR mask fgattn_forward reads.
+ *   q_avg(i) = mean of the rows of query block i (M rows), k_avg(j) = mean of the rows of key block j (N rows),
+ *   A_hat(i,:) = softmax_j(scale * <q_avg(i), k_avg(j)>); per query block the key blocks are ranked by A_hat
+ *   (equal values: lower id first) and the smallest prefix whose mass is at least top_p is kept.
+ * Reading of what the paper leaves open: the block means are bf16 tensors (fp32 sum in row order, fp32 divide,
+ * one rounding to nearest even); scores and masses are fp32 / 2^-40 fixed point.
+ *
+ * fgattn_mask_select: q, k as in fgattn_forward (strides from `p`; v/out strides ignored).  Writes
+ *   mask_indptr (device, int64 [B*H*ceil(L/M) + 1]) and keeps the per-block cut in `workspace`
+ *   (device, 256-byte aligned, at least fgattn_mask_workspace_bytes(p): block means, one fp32 score per
+ *   (query block, key block), 12 bytes per query block).  top_p must be in (0, 1] (FGATTN_E_SCALE otherwise).
+ * fgattn_mask_emit: after the caller has read nnz = mask_indptr[last] and provided mask_indices (device, int32,
+ *   capacity >= nnz entries): writes the kept key-block ids of every query block in ascending order.  Entries
+ *   that would fall beyond `indices_capacity` are dropped, never written out of bounds.  `workspace` must be the
+ *   one fgattn_mask_select filled for the same `p`.
+ * Both are asynchronous on `stream`, allocate nothing, and return FGATTN_* codes like the other calls.
+ */
+size_t fgattn_mask_workspace_bytes(const fgattn_params* p);
+int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, float top_p, int64_t* mask_indptr,
+                       void* workspace, size_t workspace_bytes, void* stream);
+int fgattn_mask_emit(const fgattn_params* p, const int64_t* mask_indptr, int32_t* mask_indices, int64_t indices_capacity,
+                     const void* workspace, size_t workspace_bytes, void* stream);
+
 /* Number of persistent workgroups fgattn_forward would launch for `p` on the current device
  * (0 on error).  Informational: used by benchmarks to report the launch shape. */
 int fgattn_grid_size(const fgattn_params* p);

@@ -53,6 +53,12 @@ def lib():
         L.fgattn_plan.restype = ctypes.c_int
         L.fgattn_validate_mask.argtypes = [i64p, vp, pp, vp, ctypes.c_size_t, vp]
         L.fgattn_validate_mask.restype = ctypes.c_int
+        L.fgattn_mask_workspace_bytes.argtypes = [pp]
+        L.fgattn_mask_workspace_bytes.restype = ctypes.c_size_t
+        L.fgattn_mask_select.argtypes = [vp, vp, pp, ctypes.c_float, vp, vp, ctypes.c_size_t, vp]
+        L.fgattn_mask_select.restype = ctypes.c_int
+        L.fgattn_mask_emit.argtypes = [pp, vp, vp, ctypes.c_int64, vp, ctypes.c_size_t, vp]
+        L.fgattn_mask_emit.restype = ctypes.c_int
         L.fgattn_grid_size.argtypes = [pp]
         L.fgattn_grid_size.restype = ctypes.c_int
         L.fgattn_strerror.argtypes = [ctypes.c_int]
@@ -115,6 +121,23 @@ def fgattn_dense_forward(q, k, v, params, out, lse, workspace, stream=None):
     _check(lib().fgattn_dense_forward(q.data_ptr(), k.data_ptr(), v.data_ptr(), ctypes.byref(params),
                                       out.data_ptr(), lse.data_ptr(), workspace.data_ptr(),
                                       workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+
+def fgattn_mask_workspace_bytes(params):
+    return int(lib().fgattn_mask_workspace_bytes(ctypes.byref(params)))
+
+
+def fgattn_mask_select(q, k, params, top_p, mask_indptr, workspace, stream=None):
+    """Top-p mask, first half: fills mask_indptr (device int64) and the per-block cuts in `workspace`."""
+    _check(lib().fgattn_mask_select(q.data_ptr(), k.data_ptr(), ctypes.byref(params), float(top_p), mask_indptr.data_ptr(),
+                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+
+def fgattn_mask_emit(params, mask_indptr, mask_indices, workspace, stream=None):
+    """Top-p mask, second half: writes the kept key-block ids (ascending per query block) into mask_indices."""
+    _check(lib().fgattn_mask_emit(ctypes.byref(params), mask_indptr.data_ptr(), mask_indices.data_ptr(),
+                                  int(mask_indices.numel()), workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
 
 
 def fgattn_plan(mask_indptr, params, workspace, stream=None):

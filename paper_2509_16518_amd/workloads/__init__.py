@@ -93,6 +93,26 @@ def make_qkv(w):
     return tuple(normal_bf16(w.seed, s, shape) for s in (1, 2, 3))
 
 
+def make_qk_local(w, gain=1.0, bandwidth=0.35):
+    """Q and K whose scores are local in space-time, as video-DiT attention is (Sec. 4.3): the N(0,1) draws of
+    make_qkv plus `gain` times seeded random Fourier features of the token's (t, h, w) grid position, so that
+    <q, k> grows towards tokens that are close on the grid.  Returns bf16 bit patterns (q, k), [B, H, L, d]."""
+    q, k, _ = make_qkv(w)
+    T, Hg, Wg = w.grid
+    assert T * Hg * Wg == w.L, "needs a token grid"
+    idx = np.arange(w.L)
+    pos = np.stack([idx // (Hg * Wg), (idx // Wg) % Hg, idx % Wg], axis=1).astype(np.float64)
+    rng = np.random.default_rng(w.seed + 77)
+    xq, xk = bf16_bits_to_f64(q), bf16_bits_to_f64(k)
+    for h in range(w.H):
+        freq = rng.normal(0.0, bandwidth, size=(3, w.d // 2))      # one draw per head, shared by Q and K
+        ang = pos @ freq
+        feat = gain * np.concatenate([np.cos(ang), np.sin(ang)], axis=1)   # <feat(a), feat(b)> = gain^2 sum cos(freq.(a-b))
+        xq[:, h] += feat
+        xk[:, h] += feat
+    return f32_to_bf16_bits(xq.astype(np.float32)), f32_to_bf16_bits(xk.astype(np.float32))
+
+
 def make_mask(w):
     """CSR mask: indptr int64 [items + 1], indices int32 [nnz] (ascending key-group ids per item)."""
     spec = _Spec(w.kind, w.B * w.H, w.L, w.M, w.N, w.grid[0], w.grid[1], w.grid[2], w.window[0], w.window[1],

@@ -1,0 +1,178 @@
+"""GPU parity of the top-p mask (paper Sec. 4.3) against the oracle, through the C ABI.
+
+What is unique is compared exactly: the bf16 block means (bit for bit), and the kept set of every
+query block whose cumulative probability clears p by more than rounding.  Where the oracle's
+fp64 cumulative sum passes p within EPS of a boundary, the fp32/fixed-point kernel may keep one
+key block more or fewer: there the kept set must still be a top set of the oracle's ranking (up to
+EPS in probability) whose mass reaches p - EPS and would not reach p + EPS without its last member.
+EPS = 1e-5 covers the fp32 accumulation of 128 exact bf16 products (relative 1e-6 on a score of
+order 1, hence on a weight), the 1-ulp exp2 and the 2^-40 fixed point.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_16518_amd import fgattn as F
+from paper_2509_16518_amd import workloads as W
+from gpu_util import Problem, check_against_oracle, say, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+EPS = 1e-5
+
+
+def gpu_mask(w, q_bits, k_bits, top_p, scale=None, want_pooled=False):
+    """Runs select + emit; returns (indptr, indices) as numpy (and the Q block means if asked)."""
+    q, k = to_dev_bf16(q_bits), to_dev_bf16(k_bits)
+    p = F.make_params(q, k, k, q, w.M, w.N, w.scale if scale is None else scale)
+    nbytes = F.fgattn_mask_workspace_bytes(p)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    rows = w.B * w.H * w.QB
+    indptr = torch.full((rows + 1,), -1, dtype=torch.int64, device="cuda")
+    F.fgattn_mask_select(q, k, p, top_p, indptr, ws)
+    nnz = int(indptr[-1].item())
+    assert nnz >= rows, "every query block keeps at least one key block"
+    indices = torch.full((nnz + 8,), -7, dtype=torch.int32, device="cuda")   # 8 guard entries behind the capacity
+    F.fgattn_mask_emit(p, indptr, indices[:nnz], ws)
+    torch.cuda.synchronize()
+    assert (indices[nnz:] == -7).all(), "emit wrote past the capacity"
+    res = (indptr.cpu().numpy(), indices[:nnz].cpu().numpy())
+    if want_pooled:
+        pooled = ws[:rows * w.d * 2].view(torch.int16).cpu().numpy().view(np.uint16).reshape(w.B * w.H, w.QB, w.d)
+        return res + (pooled,)
+    return res
+
+
+def check_rows(oracle, w, q_bits, k_bits, top_p, indptr, indices, rows, scale=None, what=""):
+    """Compares the kept sets of the given query blocks with the oracle; returns the number that differed (validly)."""
+    assert indptr[0] == 0 and np.all(np.diff(indptr) >= 1)
+    ref = oracle.topp_rows(q_bits, k_bits, w.M, w.N, w.scale if scale is None else scale, top_p, rows=rows)
+    inexact = 0
+    for row, (kept, order, cum) in zip(rows, ref):
+        got = indices[indptr[row]:indptr[row + 1]]
+        assert np.all(np.diff(got) > 0) and got[0] >= 0 and got[-1] < w.G, "%s row %d: ids not ascending / in range" % (what, row)
+        want = np.sort(order[:kept])
+        if got.size == want.size and np.array_equal(got, want):
+            continue
+        inexact += 1
+        prob = np.empty(w.G)
+        prob[order] = np.diff(np.concatenate([[0.0], cum]))
+        inside = np.zeros(w.G, dtype=bool)
+        inside[got] = True
+        lo_in, hi_out = prob[inside].min(), (prob[~inside].max() if (~inside).any() else 0.0)
+        mass = prob[inside].sum()
+        ok = lo_in >= hi_out - EPS and mass >= top_p - EPS and mass - lo_in < top_p + EPS
+        assert ok, "%s row %d: kept %d (oracle %d), mass %.9f, least kept %.3e, best dropped %.3e" % (
+            what, row, got.size, kept, mass, lo_in, hi_out)
+    say("    %s: %d rows checked, %d differ within rounding of p" % (what, len(rows), inexact))
+    return inexact
+
+
+@pytest.mark.parametrize("M,N,d,L,grid", [(16, 1, 64, 1024, (4, 16, 16)), (64, 8, 128, 1024, (4, 16, 16)),
+                                          (128, 32, 128, 1024, (4, 16, 16)), (32, 1, 128, 1000, (10, 10, 10)),
+                                          (64, 3, 64, 1000, (10, 10, 10)), (16, 1, 64, 3000, (3, 25, 40))])
+@pytest.mark.parametrize("top_p", [0.5, 0.9])
+def test_mask_matches_oracle_small(oracle_mod, M, N, d, L, grid, top_p):
+    w = W.Workload("mask-M%d-N%d-d%d-L%d" % (M, N, d, L), H=2, L=L, d=d, M=M, N=N, grid=grid, seed=4000 + M + N)
+    q, k = W.make_qk_local(w, gain=1.5 if d == 64 else 1.2)
+    say("mask %s p=%.2f" % (w.name, top_p))
+    indptr, indices, pooled = gpu_mask(w, q, k, top_p, want_pooled=True)
+    assert np.array_equal(pooled, oracle_mod.pool(q, M)), "query block means differ from the oracle's bits"
+    rows = list(range(w.items))
+    bad = check_rows(oracle_mod, w, q, k, top_p, indptr, indices, rows, what=w.name)
+    assert bad <= max(1, len(rows) // 20)
+    density = indices.size / float(w.items * w.G)
+    say("    density %.3f" % density)
+
+
+def test_mask_unstructured_inputs(oracle_mod):
+    # plain N(0,1) Q, K: nearly flat probabilities, most key blocks are kept and many masses sit close together
+    w = W.Workload("mask-flat", H=2, L=2048, d=128, M=64, N=1, seed=4100)
+    q, k, _ = W.make_qkv(w)
+    say("mask flat")
+    indptr, indices = gpu_mask(w, q, k, 0.9)
+    check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, list(range(w.items)), what=w.name)
+
+
+@pytest.mark.parametrize("L,N,top_p,kept", [(1024, 8, 0.75, 96), (8192, 1, 0.75, 6144), (8192, 1, 0.5, 4096)])
+def test_uniform_scores_closed_form(L, N, top_p, kept):
+    # Q = 0: all key blocks weigh the same, the mask is the ceil(p*G) lowest ids.  G = 128 goes through the
+    # sorted-bin path, G = 8192 through the run-of-equal-scores path (more members than fit the sort).
+    w = W.Workload("mask-uniform", H=1, L=L, d=64, M=64, N=N, seed=4200)
+    _, k, _ = W.make_qkv(w)
+    q = np.zeros_like(k)
+    say("mask uniform L=%d N=%d p=%.2f" % (L, N, top_p))
+    indptr, indices = gpu_mask(w, q, k, top_p)
+    assert np.array_equal(np.diff(indptr), np.full(w.items, kept))
+    for r in range(w.items):
+        assert np.array_equal(indices[indptr[r]:indptr[r + 1]], np.arange(kept))
+
+
+def test_dominant_key_block_and_p_one(oracle_mod):
+    w = W.Workload("mask-spike", H=1, L=512, d=64, M=32, N=4, seed=4300)
+    rng = np.random.default_rng(3)
+    q = W.f32_to_bf16_bits(np.ones((1, 1, w.L, w.d), dtype=np.float32))
+    kf = rng.uniform(-0.1, 0.1, size=(1, 1, w.L, w.d)).astype(np.float32)
+    kf[0, 0, 5 * w.N:6 * w.N] = 4.0
+    k = W.f32_to_bf16_bits(kf)
+    say("mask spike")
+    indptr, indices = gpu_mask(w, q, k, 0.9, scale=1.0)
+    assert np.array_equal(np.diff(indptr), np.ones(w.items)) and np.all(indices == 5)
+    # top_p = 1: everything that has any weight at 2^-40 resolution -- here every key block but nothing twice
+    indptr, indices = gpu_mask(w, q, k, 1.0, scale=0.05)
+    assert np.all(np.diff(indptr) <= w.G) and np.all(np.diff(indptr) >= 1)
+    check_rows(oracle_mod, w, q, k, 1.0, indptr, indices, list(range(w.items)), scale=0.05, what="p=1")
+
+
+def test_mask_feeds_forward(oracle_mod):
+    # the loop closed on the device: Q, K -> mask -> sparse attention, checked against the oracle run on that mask
+    w = W.Workload("mask-then-attend", H=2, L=1024, d=128, M=64, N=8, grid=(4, 16, 16), seed=4400)
+    q, k = W.make_qk_local(w, gain=1.2)
+    _, _, v = W.make_qkv(w)
+    say("mask -> forward")
+    indptr, indices = gpu_mask(w, q, k, 0.9)
+    prob = Problem(w, q, k, v, mask=(indptr, indices))
+    p = prob.params()
+    assert F.fgattn_validate_mask(prob.d_indptr, prob.d_indices, p, prob.workspace(p)) == 0
+    got = prob.run()
+    check_against_oracle(oracle_mod, prob, got, what=w.name)
+
+
+def test_mask_argument_checks():
+    w = W.TINY
+    q, k, _ = W.make_qkv(w)
+    dq, dk = to_dev_bf16(q), to_dev_bf16(k)
+    p = F.make_params(dq, dk, dk, dq, w.M, w.N, w.scale)
+    ws = torch.empty(F.fgattn_mask_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    indptr = torch.zeros(w.items + 1, dtype=torch.int64, device="cuda")
+    for bad_p in (0.0, -0.1, 1.5, float("nan")):
+        with pytest.raises(F.FgattnError) as e:
+            F.fgattn_mask_select(dq, dk, p, bad_p, indptr, ws)
+        assert e.value.code == F.E_SCALE
+    with pytest.raises(F.FgattnError) as e:
+        F.fgattn_mask_select(dq, dk, p, 0.9, indptr, ws[:1024])
+    assert e.value.code == F.E_WORKSPACE
+    p2 = F.make_params(dq, dk, dk, dq, 48, w.N, w.scale)
+    assert F.fgattn_mask_workspace_bytes(p2) == 0
+
+
+def test_mask_full_size_wan(oracle_mod):
+    # config-2 shape: 6144 query blocks x 32760 key blocks; sampled rows against the oracle, all rows by properties
+    w = W.WAN_1_3B
+    q, k = W.make_qk_local(w, gain=1.0)
+    say("mask wan-1.3b p=0.9")
+    indptr, indices = gpu_mask(w, q, k, 0.9)
+    nnz = np.diff(indptr)
+    say("    density %.3f, per block min %d max %d" % (indices.size / float(w.items * w.G), nnz.min(), nnz.max()))
+    d_indptr, d_indices = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    dq = to_dev_bf16(q)
+    p = F.make_params(dq, dq, dq, dq, w.M, w.N, w.scale)
+    ws = torch.empty(F.fgattn_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    assert F.fgattn_validate_mask(d_indptr, d_indices, p, ws) == 0
+    rng = np.random.default_rng(0)
+    rows = sorted({0, w.QB - 1, w.items - 1, int(np.argmax(nnz)), int(np.argmin(nnz))} |
+                  set(rng.choice(w.items, size=43, replace=False).tolist()))
+    bad = check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, what=w.name)
+    assert bad <= 5
