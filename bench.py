@@ -69,8 +69,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="wan-1.3b", choices=["wan-1.3b", "tiny"])
-    ap.add_argument("--cpu-items", type=int, default=1536, help="work items the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-items", type=int, default=3072, help="work items the oracle is timed on (0 = skip)")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-mask", dest="mask", action="store_false", help="skip timing the top-p mask kernels")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy kernel (reference for scaling rocprofv3 FETCH/WRITE_SIZE)")
     args = ap.parse_args()
@@ -162,6 +163,23 @@ def main():
                         "gather_TBps_in_full_kernel": gather_bytes / ms_main / 1e9,
                         "compute_only_pct_bf16_mfma_peak": 100.0 * useful / ms_compute / 1e9 / MFMA_BF16_PEAK_TFLOPS}
         del scratch_out, scratch_lse
+    if args.mask and w.grid[0] * w.grid[1] * w.grid[2] == w.L:
+        # the step before the hot path (Sec. 4.3): top-p mask from block means, on Q/K with space-time locality
+        log("timing the top-p mask kernels")
+        mq, mk = W.make_qk_local(w, gain=2.5)
+        dmq, dmk = dev(mq), dev(mk)
+        pm = F.make_params(dmq, dmk, dmk, dmq, w.M, w.N, w.scale)
+        mws = torch.empty(F.fgattn_mask_workspace_bytes(pm), dtype=torch.uint8, device="cuda")
+        m_indptr = torch.zeros(w.items + 1, dtype=torch.int64, device="cuda")
+        ms_select = time_calls(lambda: F.fgattn_mask_select(dmq, dmk, pm, 0.9, m_indptr, mws), 2, 5)
+        m_nnz = int(m_indptr[-1].item())
+        m_indices = torch.empty(m_nnz, dtype=torch.int32, device="cuda")
+        ms_emit = time_calls(lambda: F.fgattn_mask_emit(pm, m_indptr, m_indices, mws), 2, 5)
+        res["mask"] = {"top_p": 0.9, "select_ms": ms_select, "emit_ms": ms_emit, "density": m_nnz / float(w.items * w.G),
+                       "workspace_MB": mws.numel() / 1e6,
+                       "algorithmic_GB": (3 * w.items * w.G * 4.0 + 4.0 * m_nnz + 2.0 * w.H * w.L * w.d * 2) / 1e9,
+                       "data": "N(0,1) + random Fourier features of the token grid position (gain 2.5)"}
+        del dmq, dmk, mws, m_indices
     if not args.no_dense:
         def dense_step():
             F.fgattn_dense_forward(dq, dk, dv, p, out, lse, ws)
@@ -170,6 +188,8 @@ def main():
         res["dense"] = {"ms": ms_dense, "tflops": dense_flop / ms_dense / 1e9,
                         "pct_bf16_mfma_peak": 100.0 * dense_flop / ms_dense / 1e9 / MFMA_BF16_PEAK_TFLOPS, "steps": nd}
         res["sparse_over_dense_time"] = ms_step / ms_dense
+        if "mask" in res:
+            res["mask"]["over_dense_time"] = (res["mask"]["select_ms"] + res["mask"]["emit_ms"]) / ms_dense
     if args.cpu_items > 0:
         log("timing the oracle on %d work items" % args.cpu_items)
         res["cpu_baseline"] = cpu_baseline(w, q, k, v, indptr, indices, min(args.cpu_items, w.items))

@@ -125,7 +125,7 @@ int fgattn_validate_mask(const int64_t* mask_indptr, const int32_t* mask_indices
  * fgattn_mask_select: q, k as in fgattn_forward (strides from `p`; v/out strides ignored).  Writes
  *   mask_indptr (device, int64 [B*H*ceil(L/M) + 1]) and keeps the per-block cut in `workspace`
  *   (device, 256-byte aligned, at least fgattn_mask_workspace_bytes(p): block means, one fp32 score per
- *   (query block, key block), 12 bytes per query block).  top_p must be in (0, 1] (FGATTN_E_SCALE otherwise).
+ *   (query block, key block), 20 bytes per query block).  top_p must be in (0, 1] (FGATTN_E_SCALE otherwise).
  * fgattn_mask_emit: after the caller has read nnz = mask_indptr[last] and provided mask_indices (device, int32,
  *   capacity >= nnz entries): writes the kept key-block ids of every query block in ascending order.  Entries
  *   that would fall beyond `indices_capacity` are dropped, never written out of bounds.  `workspace` must be the

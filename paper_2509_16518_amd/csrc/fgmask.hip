@@ -34,16 +34,30 @@ constexpr int kBins = 2048;
 constexpr int kCap = 2048;          // members of the crossing bin that are sorted in LDS
 constexpr float kLog2e = 1.44269504088896340736f;
 
+__device__ __forceinline__ unsigned ordered_bits(float s) {   // monotone: larger score, larger unsigned
+  const unsigned u = __float_as_uint(s);
+  return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float from_ordered(unsigned o) {
+  const unsigned u = o ^ ((o >> 31) ? 0x80000000u : 0xFFFFFFFFu);
+  return __uint_as_float(u);
+}
 // ---------------------------------------------------------------------------------------------
 // Step 1: block means.  One thread per (block, column): the additions run in row order, so every
 // implementation of this reading produces the same bits.
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(128) pool_kernel(const uint16_t* x, int64_t sb, int64_t sh, int64_t sl, int H, int L,
-                                                    int d, int rows_per_block, int nblocks, uint16_t* pooled) {
+                                                    int d, int rows_per_block, int nblocks, uint16_t* pooled,
+                                                    unsigned* range_init) {
   const int c = threadIdx.x;
   const int blk = blockIdx.x;
   const int slice = blockIdx.y;
   if (c >= d) return;
+  // the Q pass also resets the (max, min) pair of the score row this query block will own
+  if (range_init != nullptr && c == 0) {
+    range_init[2 * ((int64_t)slice * nblocks + blk)] = 0u;
+    range_init[2 * ((int64_t)slice * nblocks + blk) + 1] = 0xFFFFFFFFu;
+  }
   const int b = slice / H, h = slice - b * H;
   const int r0 = blk * rows_per_block;
   const int r1 = min(r0 + rows_per_block, L);
@@ -62,12 +76,12 @@ __global__ void __launch_bounds__(128) pool_kernel(const uint16_t* x, int64_t sb
 // step); in the accumulator a register holds one query block and 32 consecutive key blocks across
 // lanes, so every store covers whole 128-byte lines.
 // ---------------------------------------------------------------------------------------------
-constexpr int kTilesPerWave = 8;
+constexpr int kTilesPerWave = 16;
 
 template <int D>
 __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const uint16_t* kp, int64_t k_slice_stride,
                                                       int64_t k_row_stride, int QB, int G, int Gs, float scale,
-                                                      float* scores) {
+                                                      float* scores, unsigned* range) {
   constexpr int STEPS = D / 16;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int ln = lane & 31, g = lane >> 5;
@@ -83,26 +97,57 @@ __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const u
     for (int s = 0; s < STEPS; s++) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(src + (2 * s + g) * 16));
   }
   const char* kbase = reinterpret_cast<const char*>(kp + slice * k_slice_stride);
-  for (int t = 0; t < kTilesPerWave; t++) {
-    const int key0 = (tile0 + t) * 32;
-    if (key0 >= G) break;
-    const int krow = min(key0 + ln, G - 1);
+  auto load_tile = [&](int tile, bf16x8 (&kf)[STEPS]) {
+    const int krow = min(tile * 32 + ln, G - 1);
     const char* src = kbase + (int64_t)krow * k_row_stride * 2;
-    bf16x8 kf[STEPS];
 #pragma unroll
     for (int s = 0; s < STEPS; s++) kf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(src + (2 * s + g) * 16));
+  };
+  // running range of the scores this lane produced, per accumulator register (= per query block)
+  float vmax[16], vmin[16];
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    vmax[r] = -INFINITY;
+    vmin[r] = INFINITY;
+  }
+  const int ntiles = min(kTilesPerWave, (G - tile0 * 32 + 31) / 32);
+  bf16x8 kf[STEPS], kn[STEPS];
+  load_tile(tile0, kf);
+  for (int t = 0; t < ntiles; t++) {
+    if (t + 1 < ntiles) load_tile(tile0 + t + 1, kn);   // next tile's operand in flight during this tile's MFMAs
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[r] = 0.0f;
 #pragma unroll
     for (int s = 0; s < STEPS; s++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[s], acc, 0, 0, 0);
-    const int col = key0 + ln;
+    const int col = (tile0 + t) * 32 + ln;
     if (col < G) {
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int qrow = q0 + 8 * (r / 4) + 4 * g + (r % 4);
-        if (qrow < QB) scores[((int64_t)slice * QB + qrow) * Gs + col] = acc[r] * scale;
+        const float v = acc[r] * scale;
+        vmax[r] = fmaxf(vmax[r], v);
+        vmin[r] = fminf(vmin[r], v);
+        if (qrow < QB) scores[((int64_t)slice * QB + qrow) * Gs + col] = v;
       }
+    }
+#pragma unroll
+    for (int s = 0; s < STEPS; s++) kf[s] = kn[s];
+  }
+  // one (max, min) update per query block and wave: reduce over the 32 lanes that share the block
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    float a = vmax[r], b = vmin[r];
+#pragma unroll
+    for (int off = 16; off > 0; off >>= 1) {
+      a = fmaxf(a, __shfl_xor(a, off));
+      b = fminf(b, __shfl_xor(b, off));
+    }
+    const int qrow = q0 + 8 * (r / 4) + 4 * g + (r % 4);
+    if (ln == 0 && qrow < QB && a >= b) {
+      unsigned* rr = range + 2 * ((int64_t)slice * QB + qrow);
+      atomicMax(rr, ordered_bits(a));
+      atomicMin(rr + 1, ordered_bits(b));
     }
   }
 }
@@ -110,14 +155,6 @@ __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const u
 // ---------------------------------------------------------------------------------------------
 // Step 2b + 3: selection.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ unsigned ordered_bits(float s) {   // monotone: larger score, larger unsigned
-  const unsigned u = __float_as_uint(s);
-  return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
-}
-__device__ __forceinline__ float from_ordered(unsigned o) {
-  const unsigned u = o ^ ((o >> 31) ? 0x80000000u : 0xFFFFFFFFu);
-  return __uint_as_float(u);
-}
 // rank key of key block j with score s: higher score first, then lower id first
 __device__ __forceinline__ unsigned long long rank_key(float s, int j) {
   return ((unsigned long long)ordered_bits(s) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)j);
@@ -127,12 +164,54 @@ __device__ __forceinline__ unsigned long long weight_of(float s, float rmax) {
   return (unsigned long long)(e * 1099511627776.0f);   // 2^40 fixed point, truncated
 }
 
+// Visits every score of a row: four consecutive scores per thread and step (16-byte loads; rows start 16-byte
+// aligned and their stride is a multiple of four floats), four steps in flight.
+template <typename Fn>
+__device__ __forceinline__ void for_each_score(const float* s, int G, Fn&& fn) {
+  constexpr int STEP = kSelThreads * 4;
+  auto visit = [&](const float4& v, int j4) {
+    fn(v.x, j4);
+    if (j4 + 1 < G) fn(v.y, j4 + 1);
+    if (j4 + 2 < G) fn(v.z, j4 + 2);
+    if (j4 + 3 < G) fn(v.w, j4 + 3);
+  };
+  int j4 = threadIdx.x * 4;
+  for (; j4 + 3 * STEP < G; j4 += 4 * STEP) {
+    const float4 a = *reinterpret_cast<const float4*>(s + j4);
+    const float4 b = *reinterpret_cast<const float4*>(s + j4 + STEP);
+    const float4 c = *reinterpret_cast<const float4*>(s + j4 + 2 * STEP);
+    const float4 d = *reinterpret_cast<const float4*>(s + j4 + 3 * STEP);
+    visit(a, j4);
+    visit(b, j4 + STEP);
+    visit(c, j4 + 2 * STEP);
+    visit(d, j4 + 3 * STEP);
+  }
+  for (; j4 < G; j4 += STEP) visit(*reinterpret_cast<const float4*>(s + j4), j4);
+}
+
+// Exclusive prefix of `n` over the threads of the workgroup in thread order; *total gets the sum.
+// wave_tot: four words of shared memory.  Contains two barriers.
+__device__ __forceinline__ unsigned block_exclusive(unsigned n, unsigned* wave_tot, unsigned* total) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  unsigned incl = n;
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
+  }
+  if (lane == 63) wave_tot[wv] = incl;
+  __syncthreads();
+  unsigned before = 0;
+  for (int w2 = 0; w2 < wv; w2++) before += wave_tot[w2];
+  *total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+  __syncthreads();
+  return before + incl - n;
+}
+
 struct SelShared {
   unsigned long long mass[kBins];
   unsigned cnt[kBins];
   unsigned long long cand[kCap];
   unsigned long long red64[kSelThreads];
-  float redf[2 * kSelThreads];
   unsigned long long mass_above, target, cut;
   unsigned n_above, bin, bin_cnt, ncand, klo, khi, run;
   int done;
@@ -177,32 +256,15 @@ __device__ __forceinline__ void locate_bin(SelShared& sh) {
   __syncthreads();
 }
 
-__global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores, int G, int Gs, float top_p,
-                                                             unsigned long long* cut, unsigned* count) {
+__global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores, const unsigned* range, int G, int Gs,
+                                                             float top_p, unsigned long long* cut, unsigned* count) {
   __shared__ SelShared sh;
   const int tid = threadIdx.x;
   const int64_t row = blockIdx.x;
   const float* s = scores + row * Gs;
 
-  // pass 1: range of the scores
-  float mx = -INFINITY, mn = INFINITY;
-  for (int j = tid; j < G; j += kSelThreads) {
-    const float v = s[j];
-    mx = fmaxf(mx, v);
-    mn = fminf(mn, v);
-  }
-  sh.redf[tid] = mx;
-  sh.redf[kSelThreads + tid] = mn;
-  __syncthreads();
-  for (int off = kSelThreads / 2; off > 0; off >>= 1) {
-    if (tid < off) {
-      sh.redf[tid] = fmaxf(sh.redf[tid], sh.redf[tid + off]);
-      sh.redf[kSelThreads + tid] = fminf(sh.redf[kSelThreads + tid], sh.redf[kSelThreads + tid + off]);
-    }
-    __syncthreads();
-  }
-  const float rmax = sh.redf[0], rmin = sh.redf[kSelThreads];
-  __syncthreads();
+  // range of the scores (collected by the scores kernel)
+  const float rmax = from_ordered(range[2 * row]), rmin = from_ordered(range[2 * row + 1]);
   const float width = rmax - rmin;
   const float inv = width > 0.0f ? (float)kBins / width : 0.0f;
   auto value_bin = [&](float v) -> int {   // bin 0 holds the largest scores
@@ -217,14 +279,13 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
   }
   __syncthreads();
   unsigned long long zl = 0;
-  for (int j = tid; j < G; j += kSelThreads) {
-    const float v = s[j];
+  for_each_score(s, G, [&](float v, int) {
     const unsigned long long w = weight_of(v, rmax);
     zl += w;
     const int b = value_bin(v);
     atomicAdd(&sh.mass[b], w);
     atomicAdd(&sh.cnt[b], 1u);
-  }
+  });
   const unsigned long long Z = block_sum_u64(sh, zl);
   if (tid == 0) {
     double t = ceil((double)top_p * (double)Z);
@@ -253,15 +314,14 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
     }
     __syncthreads();
     unsigned lo = 0xFFFFFFFFu, hi = 0u;
-    for (int j = tid; j < G; j += kSelThreads) {
-      const float v = s[j];
+    for_each_score(s, G, [&](float v, int) {
       const unsigned o = ordered_bits(v);
       const bool in = by_value ? (value_bin(v) == (int)bin) : (o >= klo && o <= khi);
       if (in) {
         lo = min(lo, o);
         hi = max(hi, o);
       }
-    }
+    });
     atomicMin(&sh.klo, lo);
     atomicMax(&sh.khi, hi);
     __syncthreads();
@@ -275,15 +335,14 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
       sh.cnt[i] = 0;
     }
     __syncthreads();
-    for (int j = tid; j < G; j += kSelThreads) {
-      const float v = s[j];
+    for_each_score(s, G, [&](float v, int) {
       const unsigned o = ordered_bits(v);
       if (o >= klo && o <= khi) {
         const int b = (int)(((unsigned long long)(khi - o) * kBins) / R);
         atomicAdd(&sh.mass[b], weight_of(v, rmax));
         atomicAdd(&sh.cnt[b], 1u);
       }
-    }
+    });
     __syncthreads();
     locate_bin(sh);
     // ordered bits of the new bin b: khi - o in [ceil(b*R/kBins), ceil((b+1)*R/kBins) - 1]
@@ -313,15 +372,14 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
     while (n2 < (int)bin_cnt) n2 <<= 1;
     for (int i = tid; i < n2; i += kSelThreads) sh.cand[i] = 0ull;
     __syncthreads();
-    for (int j = tid; j < G; j += kSelThreads) {
-      const float v = s[j];
+    for_each_score(s, G, [&](float v, int j) {
       const unsigned o = ordered_bits(v);
       const bool in = by_value ? (value_bin(v) == (int)bin) : (o >= klo && o <= khi);
       if (in) {
         const unsigned pos = atomicAdd(&sh.ncand, 1u);
         if (pos < (unsigned)kCap) sh.cand[pos] = rank_key(v, j);
       }
-    }
+    });
     __syncthreads();
     for (int k = 2; k <= n2; k <<= 1)
       for (int jj = k >> 1; jj > 0; jj >>= 1) {
@@ -373,27 +431,25 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
   unsigned long long t_keep = w_eq > 0 ? (need + w_eq - 1) / w_eq : (unsigned long long)bin_cnt;
   if (t_keep < 1) t_keep = 1;
   if (t_keep > bin_cnt) t_keep = bin_cnt;
-  if (tid == 0) sh.run = 0;
-  __syncthreads();
-  for (int base = 0; base < G; base += kSelThreads) {
-    const int j = base + tid;
-    const bool in = j < G && ordered_bits(s[j]) == klo;
-    // position of this member among the members of the chunk (ids ascend with tid)
-    const unsigned long long ballot = __ballot(in);
-    const int wv = tid >> 6, lane = tid & 63;
-    const unsigned before = (unsigned)__popcll(ballot & ((1ull << lane) - 1ull));
-    if (lane == 0) sh.cnt[wv] = (unsigned)__popcll(ballot);
-    __syncthreads();
-    unsigned off = sh.run;
-    for (int w2 = 0; w2 < wv; w2++) off += sh.cnt[w2];
-    if (in && (unsigned long long)(off + before + 1u) == t_keep) {
-      cut[row] = rank_key(v_eq, j);
-      count[row] = sh.n_above + (unsigned)t_keep;
+  unsigned run = 0;   // members seen in the chunks before this one (the same in every thread)
+  for (int base = 0; base < G && (unsigned long long)run < t_keep; base += kSelThreads * 4) {
+    const int j4 = base + tid * 4;
+    bool in[4] = {false, false, false, false};
+    if (j4 < G) {
+      const float4 v = *reinterpret_cast<const float4*>(s + j4);
+      in[0] = ordered_bits(v.x) == klo;
+      in[1] = j4 + 1 < G && ordered_bits(v.y) == klo;
+      in[2] = j4 + 2 < G && ordered_bits(v.z) == klo;
+      in[3] = j4 + 3 < G && ordered_bits(v.w) == klo;
     }
-    __syncthreads();
-    if (tid == 0) sh.run += sh.cnt[0] + sh.cnt[1] + sh.cnt[2] + sh.cnt[3];
-    __syncthreads();
-    if ((unsigned long long)sh.run >= t_keep) break;
+    unsigned total;
+    unsigned pos = run + block_exclusive((unsigned)in[0] + in[1] + in[2] + in[3], sh.cnt, &total);
+    for (int e = 0; e < 4; e++)
+      if (in[e] && (unsigned long long)(++pos) == t_keep) {
+        cut[row] = rank_key(v_eq, j4 + e);
+        count[row] = sh.n_above + (unsigned)t_keep;
+      }
+    run += total;
   }
 }
 
@@ -428,31 +484,39 @@ __global__ void __launch_bounds__(1024) scan_kernel(const unsigned* count, int64
 __global__ void __launch_bounds__(kSelThreads) emit_kernel(const float* scores, int G, int Gs,
                                                            const unsigned long long* cut, const int64_t* indptr,
                                                            int32_t* indices, int64_t capacity) {
-  __shared__ unsigned wave_cnt[4];
-  __shared__ unsigned run;
-  const int tid = threadIdx.x, wv = tid >> 6, lane = tid & 63;
+  __shared__ unsigned wave_tot[4];
+  const int tid = threadIdx.x;
   const int64_t row = blockIdx.x;
   const float* s = scores + row * Gs;
   const unsigned long long c = cut[row];
   const int64_t out0 = indptr[row];
-  if (tid == 0) run = 0;
-  __syncthreads();
-  for (int base = 0; base < G; base += kSelThreads) {
-    const int j = base + tid;
-    const bool keep = j < G && rank_key(s[j], j) >= c;
-    const unsigned long long ballot = __ballot(keep);
-    const unsigned before = (unsigned)__popcll(ballot & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_cnt[wv] = (unsigned)__popcll(ballot);
-    __syncthreads();
-    unsigned off = run;
-    for (int w2 = 0; w2 < wv; w2++) off += wave_cnt[w2];
-    if (keep) {
-      const int64_t pos = out0 + off + before;
-      if (pos < capacity) indices[pos] = j;
+  unsigned run = 0;
+  constexpr int STEP = kSelThreads * 4;
+  const float4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+  float4 nxt[3];   // the next three chunks are in flight while this one is ranked and written
+#pragma unroll
+  for (int i = 0; i < 3; i++) nxt[i] = i * STEP + tid * 4 < G ? *reinterpret_cast<const float4*>(s + i * STEP + tid * 4) : zero4;
+  for (int base = 0; base < G; base += STEP) {
+    const int j4 = base + tid * 4;
+    const float4 v = nxt[0];
+    nxt[0] = nxt[1];
+    nxt[1] = nxt[2];
+    nxt[2] = j4 + 3 * STEP < G ? *reinterpret_cast<const float4*>(s + j4 + 3 * STEP) : zero4;
+    bool keep[4] = {false, false, false, false};
+    if (j4 < G) {
+      keep[0] = rank_key(v.x, j4) >= c;
+      keep[1] = j4 + 1 < G && rank_key(v.y, j4 + 1) >= c;
+      keep[2] = j4 + 2 < G && rank_key(v.z, j4 + 2) >= c;
+      keep[3] = j4 + 3 < G && rank_key(v.w, j4 + 3) >= c;
     }
-    __syncthreads();
-    if (tid == 0) run += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
-    __syncthreads();
+    unsigned total;
+    int64_t pos = out0 + run + block_exclusive((unsigned)keep[0] + keep[1] + keep[2] + keep[3], wave_tot, &total);
+    for (int e = 0; e < 4; e++)
+      if (keep[e]) {
+        if (pos < capacity) indices[pos] = j4 + e;
+        pos++;
+      }
+    run += total;
   }
 }
 
@@ -461,7 +525,7 @@ __global__ void __launch_bounds__(kSelThreads) emit_kernel(const float* scores, 
 // ---------------------------------------------------------------------------------------------
 struct Layout {
   int64_t rows, QB, G, Gs, slices;
-  size_t qp_off, kp_off, scores_off, cut_off, count_off, total;
+  size_t qp_off, kp_off, scores_off, cut_off, count_off, range_off, total;
 };
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -489,6 +553,8 @@ static int layout_of(const fgattn_params* p, Layout* lo) {
   off = align256(off + (size_t)lo->rows * 8);
   lo->count_off = off;
   off = align256(off + (size_t)lo->rows * 4);
+  lo->range_off = off;
+  off = align256(off + (size_t)lo->rows * 8);
   lo->total = off;
   return FGATTN_OK;
 }
@@ -542,11 +608,12 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
   float* scores = reinterpret_cast<float*>(ws + lo.scores_off);
   unsigned long long* cut = reinterpret_cast<unsigned long long*>(ws + lo.cut_off);
   unsigned* count = reinterpret_cast<unsigned*>(ws + lo.count_off);
+  unsigned* range = reinterpret_cast<unsigned*>(ws + lo.range_off);
   const uint16_t* qx = static_cast<const uint16_t*>(q);
   const uint16_t* kx = static_cast<const uint16_t*>(k);
 
   hipLaunchKernelGGL(pool_kernel, dim3((unsigned)lo.QB, (unsigned)lo.slices), dim3(128), 0, stream, qx, p->q_stride_b,
-                     p->q_stride_h, p->q_stride_l, p->H, p->L, p->d, p->M, (int)lo.QB, qp);
+                     p->q_stride_h, p->q_stride_l, p->H, p->L, p->d, p->M, (int)lo.QB, qp, range);
   if (!launched()) return FGATTN_E_DEVICE;
   const uint16_t* kmat = kx;
   int64_t k_slice_stride = 0, k_row_stride = p->k_stride_l;
@@ -555,7 +622,7 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
     k_slice_stride = p->k_stride_h;
   } else {
     hipLaunchKernelGGL(pool_kernel, dim3((unsigned)lo.G, (unsigned)lo.slices), dim3(128), 0, stream, kx, p->k_stride_b,
-                       p->k_stride_h, p->k_stride_l, p->H, p->L, p->d, p->N, (int)lo.G, kp);
+                       p->k_stride_h, p->k_stride_l, p->H, p->L, p->d, p->N, (int)lo.G, kp, static_cast<unsigned*>(nullptr));
     if (!launched()) return FGATTN_E_DEVICE;
     kmat = kp;
     k_slice_stride = lo.G * p->d;
@@ -565,13 +632,13 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
                    (unsigned)lo.slices);
   if (p->d == 128)
     hipLaunchKernelGGL(scores_kernel<128>, sgrid, dim3(256), 0, stream, qp, kmat, k_slice_stride, k_row_stride, (int)lo.QB,
-                       (int)lo.G, (int)lo.Gs, p->scale, scores);
+                       (int)lo.G, (int)lo.Gs, p->scale, scores, range);
   else
     hipLaunchKernelGGL(scores_kernel<64>, sgrid, dim3(256), 0, stream, qp, kmat, k_slice_stride, k_row_stride, (int)lo.QB,
-                       (int)lo.G, (int)lo.Gs, p->scale, scores);
+                       (int)lo.G, (int)lo.Gs, p->scale, scores, range);
   if (!launched()) return FGATTN_E_DEVICE;
-  hipLaunchKernelGGL(select_kernel, dim3((unsigned)lo.rows), dim3(kSelThreads), 0, stream, scores, (int)lo.G, (int)lo.Gs,
-                     top_p, cut, count);
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)lo.rows), dim3(kSelThreads), 0, stream, scores, range, (int)lo.G,
+                     (int)lo.Gs, top_p, cut, count);
   if (!launched()) return FGATTN_E_DEVICE;
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, count, lo.rows, mask_indptr);
   return launched() ? FGATTN_OK : FGATTN_E_DEVICE;
