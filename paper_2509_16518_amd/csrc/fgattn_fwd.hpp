@@ -396,9 +396,21 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     // gathers, one per MFMA slot: V rows of the current tile (keys in keyA) -> the V slot this phase does not
     // read, then K rows of the tile after next (keys in keyC) -> the K slot whose tile was multiplied during the
     // previous iteration.
-    auto pv_phase = [&](auto vslot, const i32x4 (&Pin)[2], auto with_gather) {
+    auto pv_phase = [&](auto vslot, const i32x4 (&Pin)[2], auto with_gather, auto with_qk, f32x16& Sn) {
       constexpr bool GATHER = decltype(with_gather)::value;
+      constexpr bool QK = decltype(with_qk)::value && PART != PART_GATHER;   // also Sn = K(slot vslot) Q^T
       const unsigned char* vst = smem + (2 + vslot) * C::TENSOR_BYTES;
+      const unsigned char* kst = smem + vslot * C::TENSOR_BYTES;
+      auto read_kf = [&](int s) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kst + (kor ^ (32 * s))));
+      };
+      bf16x8 kf[NE];
+      if constexpr (QK) {
+#pragma unroll
+        for (int e = 0; e < AHEAD; e++) kf[e] = read_kf(e);
+#pragma unroll
+        for (int r = 0; r < 16; r++) Sn[r] = 0.0f;
+      }
       const bf16x8 pin[2] = {__builtin_bit_cast(bf16x8, Pin[0]), __builtin_bit_cast(bf16x8, Pin[1])};
       bf16x8 vf[NE];
 #pragma unroll
@@ -409,6 +421,10 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         if constexpr (PART != PART_GATHER) {
           if constexpr (e + AHEAD < NE) vf[e + AHEAD] = read_vf(vst, e + AHEAD);
           O[e >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[e], pin[e & 1], O[e >> 1], 0, 0, 0);
+        }
+        if constexpr (QK) {
+          if constexpr (e + AHEAD < NE) kf[e + AHEAD] = read_kf(e + AHEAD);
+          Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[e], qf[e], Sn, 0, 0, 0);
         }
         if constexpr (GATHER) {
           if constexpr (e % DMA_EVERY == 0) {
@@ -439,8 +455,10 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     // run on the vector ALU in the shadow of the dependent MFMA chain: P = exp2(c*(So - m)), row sum, bf16 pack
     // into Pout.  Then the row max of the new scores and the rare decision to move the exponent base (see
     // kLazyLog2).  Also rotates the key-row sets (t+1 -> t, t+2 -> t+1).
-    auto qk_phase = [&](auto kslot, int Tm, f32x16& Sn, const f32x16& So, i32x4 (&Pout)[2], auto with_exp) {
+    auto qk_phase = [&](auto kslot, int Tm, f32x16& Sn, const f32x16& So, i32x4 (&Pout)[2], auto with_exp,
+                        auto with_mfma) {
       constexpr bool EXP = decltype(with_exp)::value;
+      constexpr bool MFMA = decltype(with_mfma)::value;
       if constexpr (PART == PART_GATHER) {   // only the bookkeeping the gathers depend on
 #pragma unroll
         for (int i = 0; i < C::IPW; i++) {
@@ -457,14 +475,18 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       const float neg_mc = -m_safe * a.c_log2;
       float psum0 = 0.0f, psum1 = 0.0f;
       bf16x8 kf[NE];
+      if constexpr (MFMA) {
 #pragma unroll
-      for (int e = 0; e < AHEAD; e++) kf[e] = read_kf(e);
+        for (int e = 0; e < AHEAD; e++) kf[e] = read_kf(e);
 #pragma unroll
-      for (int r = 0; r < 16; r++) Sn[r] = 0.0f;
+        for (int r = 0; r < 16; r++) Sn[r] = 0.0f;
+      }
       auto slot = [&](auto ec) {
         constexpr int e = decltype(ec)::value;
-        if constexpr (e + AHEAD < NE) kf[e + AHEAD] = read_kf(e + AHEAD);
-        Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[e], qf[e], Sn, 0, 0, 0);
+        if constexpr (MFMA) {
+          if constexpr (e + AHEAD < NE) kf[e + AHEAD] = read_kf(e + AHEAD);
+          Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[e], qf[e], Sn, 0, 0, 0);
+        }
         if constexpr (EXP) {
 #pragma unroll
           for (int x = 0; x < VPS; x += 2) {
@@ -532,14 +554,14 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       }
       make_keys(min(t + 2, last));        // ids fetched during the previous iteration -> keyC
       fetch_ids(min(t + 3, last));
-      pv_phase(std::integral_constant<int, PAR ^ 1>(), Pin, yes());
+      pv_phase(std::integral_constant<int, PAR ^ 1>(), Pin, yes(), yes(), Sn);
       if (__builtin_expect(resc, 0)) {
 #pragma unroll
         for (int db = 0; db < C::DBLK; db++)
 #pragma unroll
           for (int r = 0; r < 16; r++) O[db][r] *= alpha;
       }
-      qk_phase(std::integral_constant<int, PAR ^ 1>(), min(t + 1, last), Sn, So, Pout, yes());
+      qk_phase(std::integral_constant<int, PAR ^ 1>(), min(t + 1, last), Sn, So, Pout, yes(), no());
     };
 
     if (ntiles > 0) {
@@ -588,7 +610,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       wait_vmem_all();
       __syncthreads();
       // S(0) from K slot 0; keyA/keyB end up as keys(0)/keys(1)
-      qk_phase(std::integral_constant<int, 0>(), 0, SA, SA, PA, no());
+      qk_phase(std::integral_constant<int, 0>(), 0, SA, SA, PA, no(), yes());
       m_run = m_pend;   // O = 0 and l = 0 so far: the first exponent base needs no rescale
       resc = false;
       int t = 0;
@@ -599,8 +621,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       if (t < ntiles) iteration(t, std::integral_constant<int, 0>(), PB, PA, SB, SA);
       wait_vmem_all();
       __syncthreads();
-      if ((ntiles & 1) == 0) pv_phase(std::integral_constant<int, 1>(), PB, no());
-      else pv_phase(std::integral_constant<int, 0>(), PA, no());
+      if ((ntiles & 1) == 0) pv_phase(std::integral_constant<int, 1>(), PB, no(), no(), SA);
+      else pv_phase(std::integral_constant<int, 0>(), PA, no(), no(), SA);
     }
 
     // ---------------- epilogue ----------------
