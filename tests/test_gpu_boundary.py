@@ -60,3 +60,28 @@ def test_validate_mask_flags_bad_masks():
     assert F.fgattn_validate_mask(prob.d_indptr, neg, p, ws) == F.E_MASK
     dec = prob.d_indptr.clone(); dec[3] = dec[2] - 1
     assert F.fgattn_validate_mask(dec, prob.d_indices, p, ws) == F.E_MASK
+
+
+def test_forward_part_is_a_measurement_aid_only():
+    # built for M = 64, d = 128, N = 1 only; runs, leaves the real entry point's results untouched afterwards
+    w = W.Workload("part", H=2, L=2048, d=128, M=64, N=1, kind=W.MASK_RANDOM, density=0.3, seed=5100)
+    prob = Problem(w)
+    p = prob.params(flags=F.FLAG_REUSE_PLAN)
+    ws = prob.workspace(p)
+    F.fgattn_plan(prob.d_indptr, p, ws)
+    scratch_out, scratch_lse = torch.empty_like(prob.out), torch.empty_like(prob.lse)
+    for part in (F.PART_GATHER, F.PART_COMPUTE):
+        F.fgattn_forward_part(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, scratch_out, scratch_lse, ws, part)
+    torch.cuda.synchronize()
+    expect(F.E_FLAGS, lambda: F.fgattn_forward_part(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, scratch_out,
+                                                    scratch_lse, ws, 3))
+    tiny = Problem(W.TINY)
+    pt = tiny.params()
+    expect(F.E_SHAPE, lambda: F.fgattn_forward_part(tiny.q, tiny.k, tiny.v, tiny.d_indptr, tiny.d_indices, pt, tiny.out,
+                                                    tiny.lse, tiny.workspace(pt), F.PART_GATHER))
+    # the stored order is still usable: the partial kernels rewind the queue like the full one
+    F.fgattn_forward(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, prob.out, prob.lse, ws)
+    torch.cuda.synchronize()
+    a = prob.out.clone()
+    got = prob.run()
+    assert torch.equal(a, prob.out)
