@@ -102,6 +102,25 @@ int fgattn_forward_part(const void* q, const void* k, const void* v, const int64
                         const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* workspace,
                         size_t workspace_bytes, int part, void* stream);
 
+/*
+ * Sparse forward pass over GROUPED query tiles (paper Sec. 4.2 "Grouping Query Tiles Attending to Similar Sets of
+ * Keys/Values"): R = 128 / M query tiles of M rows form one work item that gathers the UNION of their key lists
+ * once; every tile still attends only to its own key blocks (the result equals fgattn_forward's on the
+ * ungrouped mask).  With G_s = ceil(ceil(L/M) / R) groups per (batch, head) slice:
+ *   group_tiles   : int32 [B*H*G_s * R]: the member tiles of each group as tile indices inside the slice
+ *                   (tile t covers rows [t*M, (t+1)*M)); -1 = no member in this position; every tile of a slice
+ *                   must appear exactly once.
+ *   union_indptr  : int64 [B*H*G_s + 1], union_indices: int32 key-block ids of each group's union (any order, no
+ *                   duplicates), union_members: uint8, one per entry of union_indices: bit r set iff member r of
+ *                   the group selected that key block.
+ * Everything else as in fgattn_forward (same workspace size; FGATTN_FLAG_REUSE_PLAN refers to a plan made by
+ * this call).  Contents of the four arrays are not checked.
+ */
+int fgattn_forward_grouped(const void* q, const void* k, const void* v, const int32_t* group_tiles,
+                           const int64_t* union_indptr, const int32_t* union_indices, const uint8_t* union_members,
+                           const fgattn_params* p, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                           void* stream);
+
 /* Only the ordering pre-pass of fgattn_forward (Appendix B: cost of an item = length of its
  * key/value list; longest first): fills `workspace`.  A later fgattn_forward with
  * FGATTN_FLAG_REUSE_PLAN and the same mask/params skips it. */

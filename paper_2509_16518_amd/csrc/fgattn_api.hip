@@ -181,10 +181,10 @@ static int check_workspace(const fgattn_params* p, const void* workspace, size_t
   return FGATTN_OK;
 }
 
-static int run_plan(const int64_t* indptr, const fgattn_params* p, void* workspace, hipStream_t stream) {
+static int run_plan(const int64_t* indptr, const fgattn_params* p, void* workspace, hipStream_t stream, int QB = 0) {
   int32_t* ctrl = static_cast<int32_t*>(workspace);
   int32_t* order = ctrl + 64;
-  const int QB = (p->L + p->M - 1) / p->M;
+  if (QB == 0) QB = (p->L + p->M - 1) / p->M;
   const int sorted = (p->flags & (FGATTN_FLAG_STATIC_ASSIGN | FGATTN_FLAG_FIFO_QUEUE)) ? 0 : 1;
   hipLaunchKernelGGL(plan_kernel, dim3(p->B * p->H), dim3(kPlanThreads), 0, stream, indptr, ctrl, order, QB, sorted);
   return hipGetLastError() == hipSuccess ? FGATTN_OK : FGATTN_E_DEVICE;
@@ -192,7 +192,8 @@ static int run_plan(const int64_t* indptr, const fgattn_params* p, void* workspa
 
 static int run_forward(const void* q, const void* k, const void* v, const int64_t* indptr, const int32_t* indices,
                        const fgattn_params* p, void* out, float* lse, void* workspace, size_t workspace_bytes,
-                       void* stream_v, int part = 0) {
+                       void* stream_v, int part = 0, const int32_t* group_tiles = nullptr,
+                       const uint8_t* group_memb = nullptr) {
   int rc = check_shape(p);
   if (rc) return rc;
   rc = check_tensors(q, k, v, out, lse, p);
@@ -203,8 +204,12 @@ static int run_forward(const void* q, const void* k, const void* v, const int64_
   rc = device_info(&dev);
   if (rc) return rc;
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  const bool grouped = group_tiles != nullptr;
+  const int R = grouped ? 128 / p->M : 1;                                   // member tiles per group
+  const int QB_tiles = (p->L + p->M - 1) / p->M;
+  const int QB_items = grouped ? (QB_tiles + R - 1) / R : QB_tiles;         // work items per (batch, head) slice
   if (!(p->flags & FGATTN_FLAG_REUSE_PLAN)) {
-    rc = run_plan(indptr, p, workspace, stream);
+    rc = run_plan(indptr, p, workspace, stream, QB_items);
     if (rc) return rc;
   }
   FwdArgs a;
@@ -223,14 +228,18 @@ static int run_forward(const void* q, const void* k, const void* v, const int64_
   a.o_sb = p->o_stride_b; a.o_sh = p->o_stride_h; a.o_sl = p->o_stride_l;
   a.H = p->H;
   a.L = p->L;
-  a.M = p->M;
+  a.M = grouped ? 128 : p->M;
   a.N = indptr ? p->N : 1;
-  const int NT = p->M <= 32 ? 128 : p->M == 64 ? 64 : 32;   // keys per LDS tile of the variant launched for M
+  a.group_tiles = group_tiles;
+  a.memb = group_memb;
+  a.tile_rows = p->M;
+  a.R = R;
+  const int NT = a.M <= 32 ? 128 : a.M == 64 ? 64 : 32;   // keys per LDS tile of the variant launched for M
   a.nt_div_n = NT / a.N;
   a.nt_mod_n = NT % a.N;
   a.n_recip16 = (65536u + (uint32_t)a.N - 1) / (uint32_t)a.N;
-  a.QB = (p->L + p->M - 1) / p->M;
-  a.n_items = (int32_t)n_items_of(p);
+  a.QB = QB_items;
+  a.n_items = (int32_t)((int64_t)p->B * p->H * QB_items);
   a.static_assign = (p->flags & FGATTN_FLAG_STATIC_ASSIGN) ? 1 : 0;
   const float sabs = fabsf(p->scale);
   // scale = 0 is run with a tiny positive exponent factor: valid keys still get p = exp2(tiny * s) = 1 exactly,
@@ -240,6 +249,7 @@ static int run_forward(const void* q, const void* k, const void* v, const int64_
   a.scale_abs = sabs;
   a.q_sign = p->scale < 0.0f ? 0x80008000u : 0u;
   if (part != 0) return launch_part(a, part, dev.cus, stream);
+  if (grouped) return launch_grouped(a, p->d, dev.cus, stream);
   return launch_forward(a, p->d, dev.cus, stream, nullptr);
 }
 
@@ -271,6 +281,15 @@ int fgattn_forward_part(const void* q, const void* k, const void* v, const int64
   if (part != FGATTN_PART_GATHER && part != FGATTN_PART_COMPUTE) return FGATTN_E_FLAGS;
   if (p && (p->M != 64 || p->d != 128 || p->N != 1)) return FGATTN_E_SHAPE;
   return fg::run_forward(q, k, v, mask_indptr, mask_indices, p, out, lse, workspace, workspace_bytes, stream, part);
+}
+
+int fgattn_forward_grouped(const void* q, const void* k, const void* v, const int32_t* group_tiles,
+                           const int64_t* union_indptr, const int32_t* union_indices, const uint8_t* union_members,
+                           const fgattn_params* p, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  if (!group_tiles || !union_indptr || !union_indices || !union_members) return FGATTN_E_NULL;
+  return fg::run_forward(q, k, v, union_indptr, union_indices, p, out, lse, workspace, workspace_bytes, stream, 0,
+                         group_tiles, union_members);
 }
 
 int fgattn_plan(const int64_t* mask_indptr, const fgattn_params* p, void* workspace, size_t workspace_bytes,

@@ -23,6 +23,11 @@ struct FwdArgs {
   float c_log2;      // |scale| * log2(e): exp(scale*s) == exp2(c_log2 * s')
   float scale_abs;   // |scale|
   uint32_t q_sign;   // 0x80008000 if scale < 0 (the sign is moved onto Q, exactly), else 0
+  // grouped query tiles (Sec. 4.2): M is then the group's rows (128), QB the groups per slice, indptr / indices the
+  // union lists; tile_rows = rows of one member tile, R = members per group
+  const int32_t* group_tiles;   // [n_items * R] member tile ids inside the slice, -1 = no tile
+  const uint8_t* memb;          // [nnz of the union lists] member bit masks
+  int32_t tile_rows, R;
 };
 
 // Launches the forward kernel variant for (a.M, d) on `stream` with a persistent grid sized to
@@ -32,6 +37,9 @@ int launch_forward(const FwdArgs& a, int d, int cus, hipStream_t stream, int* gr
 
 // Gather-only (part = 1) or compute-only (part = 2) instantiation of the M = 64, d = 128, N = 1 variant.
 int launch_part(const FwdArgs& a, int part, int cus, hipStream_t stream);
+
+// Grouped query tiles: the 128-row variant with membership masks (d = 64 / 128; N = 1 or N > 1).
+int launch_grouped(const FwdArgs& a, int d, int cus, hipStream_t stream);
 
 // One translation unit per query-tile size keeps compile times parallel.
 int launch_mt32(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only);

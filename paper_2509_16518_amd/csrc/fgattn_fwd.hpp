@@ -139,9 +139,19 @@ struct FwdCfg {
 // Online softmax of one 32-key x 32-query score block held as an MFMA accumulator: one query per
 // lane (registers 8c..8c+7 of the accumulator are the keys 16c + 8*(e/4) + 4*(lane/32) + e%4).
 // First half: mask padded keys, new running max of this lane's query.
+// MEMBER >= 0 (grouped query tiles): the row holds, per key, the bit mask of the group members that selected it;
+// a query of member MEMBER keeps only the keys whose bit is set.
 template <bool MASKED>
-__device__ __forceinline__ void softmax_max(f32x16& S, const float* bias_keys, int g, float m_run, float& m_new) {
-  if (MASKED) {
+__device__ __forceinline__ void softmax_max(f32x16& S, const float* bias_keys, int g, float m_run, float& m_new,
+                                            int member = -1) {
+  if (MASKED && member >= 0) {
+#pragma unroll
+    for (int r4 = 0; r4 < 4; r4++) {
+      i32x4 bv = *reinterpret_cast<const i32x4*>(bias_keys + 8 * r4 + 4 * g);
+#pragma unroll
+      for (int e = 0; e < 4; e++) S[4 * r4 + e] = ((bv[e] >> member) & 1) ? S[4 * r4 + e] : -INFINITY;
+    }
+  } else if (MASKED) {
     // bias is 0 for a real key and -inf for a padded / out-of-range one
 #pragma unroll
     for (int r4 = 0; r4 < 4; r4++) {
@@ -168,10 +178,15 @@ enum { NMODE_DENSE = 0, NMODE_N1 = 1, NMODE_GROUPS = 2 };
 // the two halves of the kernel can be timed apart on the same launch shape).
 enum { PART_ALL = 0, PART_GATHER = 1, PART_COMPUTE = 2 };
 
-template <int MT, int D, int NMODE, int OCC, int PART = PART_ALL>
+// GROUPED (paper Sec. 4.2): a work item is a GROUP of query tiles (a.tile_rows rows each, R = MT / tile_rows of
+// them, listed in a.group_tiles) that shares one gathered key list -- the union of the members' lists -- while
+// every member attends only to its own key blocks: a.memb holds, per entry of the union list, the bit mask of the
+// members that selected it, and scores of the others are set to -inf before the softmax.
+template <int MT, int D, int NMODE, int OCC, int PART = PART_ALL, bool GROUPED = false>
 __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
   using C = FwdCfg<MT, D>;
   constexpr bool DENSE = NMODE == NMODE_DENSE;
+  static_assert(!GROUPED || (MT == 128 && NMODE != NMODE_DENSE), "groups are 128 query rows with a sparse list");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   __shared__ int s_item;
 
@@ -237,6 +252,17 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     const int b = slice / a.H, h = slice - b * a.H;
     const int row0 = qi * a.M;
     const int row_end = min(row0 + a.M, a.L);
+    // this lane's query row; in a group the 32 rows of a wave come from the member tiles' own positions
+    int my_row = row0 + rw * 32 + ln;
+    bool my_row_valid = my_row < row_end;
+    int my_member = 0;   // which member of the group this lane's query belongs to
+    if constexpr (GROUPED) {
+      const int qg = rw * 32 + ln;
+      my_member = qg / a.tile_rows;
+      const int tile = a.group_tiles[(int64_t)w * a.R + my_member];
+      my_row = tile * a.tile_rows + (qg - my_member * a.tile_rows);
+      my_row_valid = tile >= 0 && my_row < a.L;
+    }
     int64_t beg = 0;
     int cnt;  // active key groups of this item
     if (DENSE) {
@@ -254,7 +280,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     // ---------------- Q fragment (B operand of S^T), once per item ----------------
     bf16x8 qf[C::SSTEPS];
     {
-      int qrow = min(row0 + rw * 32 + ln, a.L - 1);
+      int qrow = GROUPED ? (my_row_valid ? my_row : 0) : min(my_row, a.L - 1);
       const char* qp = reinterpret_cast<const char*>(a.q + b * a.q_sb + h * a.q_sh + (int64_t)qrow * a.q_sl);
 #pragma unroll
       for (int s = 0; s < C::SSTEPS; s++) {
@@ -273,13 +299,17 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     // Past the end of the list the pipeline keeps running on the last tile again (clamped tile index): a few
     // redundant, in-bounds gathers per work item instead of existence checks in every iteration.
     int gi[C::IPW];       // group ids being fetched (next tile to convert)
+    int gm[C::IPW];       // GROUPED: their membership masks
     int wi[C::IPW];       // offset of the key inside its group (NMODE_GROUPS)
     int widx = 0;         // coalesced id fetch: lane j holds the id of row j % RPW of this wave's rows
     int keyA[C::IPW], keyB[C::IPW], keyC[C::IPW];   // key rows of tiles t, t+1, t+2 in iteration t
     int tq = 0, tr = 0;   // (T*NT) / N and (T*NT) % N for the next tile to fetch ids for, advanced without divisions
     const int lpos = wv * C::RPW + lrow;
     const int last = ntiles - 1;
-    auto tile_needs_check = [&](int T) { return short_group || (T + 1) * C::NT > total; };
+    const uint8_t* memb = GROUPED ? a.memb + beg : nullptr;
+    // a tile whose positions need a per-key entry in the bias row: short last group, ragged last tile, or (GROUPED)
+    // always, since the row then carries the membership masks
+    auto tile_needs_check = [&](int T) { return GROUPED || short_group || (T + 1) * C::NT > total; };
     // full tiles with one key per group: one coalesced load per wave brings the RPW ids of its rows;
     // a cross-lane permute then hands each lane the id of its own row
     auto coalesced_ids = [&](int T) { return NMODE == NMODE_N1 && !tile_needs_check(T); };
@@ -301,6 +331,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
           wi[i] = x - q * N;
         }
         gi[i] = idx[min(grp, cnt - 1)];
+        if constexpr (GROUPED) gm[i] = memb[min(grp, cnt - 1)];
       }
       if (NMODE == NMODE_GROUPS && T < last) {   // a repeated (clamped) last tile must see the same tq, tr again
         tq += a.nt_div_n;
@@ -327,7 +358,12 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         if (__builtin_expect(checked, 0)) {
           const bool ok = p < total && key < a.L;
           key = ok ? key : 0;
-          if (pc == 0) bias[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? 0.0f : -INFINITY;
+          if (pc == 0) {
+            if constexpr (GROUPED)
+              reinterpret_cast<int*>(bias)[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? gm[i] : 0;
+            else
+              bias[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? 0.0f : -INFINITY;
+          }
         }
         keyC[i] = key;
       }
@@ -525,7 +561,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       }
       float m_new;
       if (__builtin_expect(tile_needs_check(Tm), 0))
-        softmax_max<true>(Sn, bias + (Tm & 1) * C::NT + kw * 32, g, m_pend, m_new);
+        softmax_max<true>(Sn, bias + (Tm & 1) * C::NT + kw * 32, g, m_pend, m_new, GROUPED ? my_member : -1);
       else
         softmax_max<false>(Sn, nullptr, g, m_pend, m_new);
       m_pend = m_new;
@@ -659,8 +695,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       }
     }
     if (kw == 0) {
-      const int row = row0 + rw * 32 + ln;
-      if (row < row_end) {
+      const int row = my_row;
+      if (my_row_valid) {
         const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
         uint16_t* op = a.out + b * a.o_sb + h * a.o_sh + (int64_t)row * a.o_sl;
 #pragma unroll

@@ -47,6 +47,8 @@ def lib():
         L.fgattn_forward.restype = ctypes.c_int
         L.fgattn_forward_part.argtypes = [vp, vp, vp, i64p, vp, pp, vp, vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
         L.fgattn_forward_part.restype = ctypes.c_int
+        L.fgattn_forward_grouped.argtypes = [vp, vp, vp, vp, i64p, vp, vp, pp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.fgattn_forward_grouped.restype = ctypes.c_int
         L.fgattn_dense_forward.argtypes = [vp, vp, vp, pp, vp, vp, vp, ctypes.c_size_t, vp]
         L.fgattn_dense_forward.restype = ctypes.c_int
         L.fgattn_plan.argtypes = [i64p, pp, vp, ctypes.c_size_t, vp]
@@ -107,6 +109,15 @@ def fgattn_forward(q, k, v, mask_indptr, mask_indices, params, out, lse, workspa
 
 
 PART_GATHER, PART_COMPUTE = 1, 2
+
+
+def fgattn_forward_grouped(q, k, v, group_tiles, union_indptr, union_indices, union_members, params, out, lse, workspace,
+                           stream=None):
+    """Sparse forward pass over grouped query tiles (union key lists with per-member masks)."""
+    _check(lib().fgattn_forward_grouped(q.data_ptr(), k.data_ptr(), v.data_ptr(), group_tiles.data_ptr(),
+                                        union_indptr.data_ptr(), union_indices.data_ptr(), union_members.data_ptr(),
+                                        ctypes.byref(params), out.data_ptr(), lse.data_ptr(), workspace.data_ptr(),
+                                        workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
 
 
 def fgattn_forward_part(q, k, v, mask_indptr, mask_indices, params, out, lse, workspace, part, stream=None):
