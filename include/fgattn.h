@@ -121,6 +121,32 @@ int fgattn_forward_grouped(const void* q, const void* k, const void* v, const in
                            const fgattn_params* p, void* out, float* lse, void* workspace, size_t workspace_bytes,
                            void* stream);
 
+/*
+ * Grouping pre-pass for fgattn_forward_grouped (paper Sec. 4.2), on the device.
+ *   mode FGATTN_GROUP_CONSECUTIVE: R = 128/M consecutive query tiles per group ("merge-consecutive", Sec. 5);
+ *   mode FGATTN_GROUP_XOR: the section's greedy heuristic on the distance d(i,j) = number of key blocks selected
+ *     by exactly one of the tiles i, j: the first ungrouped tile of a (batch, head) slice becomes a group's
+ *     representative and takes the R-1 ungrouped tiles closest to it (equal distances: lower index first;
+ *     members are listed representative first, then by (distance, index); the last group of a slice may be short).
+ * fgattn_group_select: reads the ungrouped CSR mask (as given to fgattn_forward; ids are not checked), writes
+ *   group_tiles (int32 [B*H*G_s*R], -1 padding) and union_indptr (int64 [B*H*G_s + 1]); `workspace` (device,
+ *   256-byte aligned, >= fgattn_group_workspace_bytes(p, mode)) keeps the bit rows for the second call
+ *   (one bit per (query tile, key block), plus 4 bytes per pair of query tiles of a slice in XOR mode).
+ * fgattn_group_emit: after the caller has read nnz = union_indptr[last]: writes union_indices (ascending ids per
+ *   group) and union_members; entries beyond `capacity` are dropped, never written out of bounds.
+ * Limits: ceil(L/N) <= 491520 key blocks, ceil(L/M) <= 49152 query tiles per slice (else FGATTN_E_SHAPE); an unknown
+ * mode gives FGATTN_E_FLAGS.  Asynchronous on `stream`, no allocation.
+ */
+#define FGATTN_GROUP_CONSECUTIVE 0
+#define FGATTN_GROUP_XOR 1
+size_t fgattn_group_workspace_bytes(const fgattn_params* p, int mode);
+int fgattn_group_select(const int64_t* mask_indptr, const int32_t* mask_indices, const fgattn_params* p, int mode,
+                        int32_t* group_tiles, int64_t* union_indptr, void* workspace, size_t workspace_bytes,
+                        void* stream);
+int fgattn_group_emit(const fgattn_params* p, int mode, const int32_t* group_tiles, const int64_t* union_indptr,
+                      int32_t* union_indices, uint8_t* union_members, int64_t capacity, const void* workspace,
+                      size_t workspace_bytes, void* stream);
+
 /* Only the ordering pre-pass of fgattn_forward (Appendix B: cost of an item = length of its
  * key/value list; longest first): fills `workspace`.  A later fgattn_forward with
  * FGATTN_FLAG_REUSE_PLAN and the same mask/params skips it. */

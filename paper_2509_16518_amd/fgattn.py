@@ -61,6 +61,12 @@ def lib():
         L.fgattn_mask_select.restype = ctypes.c_int
         L.fgattn_mask_emit.argtypes = [pp, vp, vp, ctypes.c_int64, vp, ctypes.c_size_t, vp]
         L.fgattn_mask_emit.restype = ctypes.c_int
+        L.fgattn_group_workspace_bytes.argtypes = [pp, ctypes.c_int]
+        L.fgattn_group_workspace_bytes.restype = ctypes.c_size_t
+        L.fgattn_group_select.argtypes = [i64p, vp, pp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        L.fgattn_group_select.restype = ctypes.c_int
+        L.fgattn_group_emit.argtypes = [pp, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int64, vp, ctypes.c_size_t, vp]
+        L.fgattn_group_emit.restype = ctypes.c_int
         L.fgattn_grid_size.argtypes = [pp]
         L.fgattn_grid_size.restype = ctypes.c_int
         L.fgattn_strerror.argtypes = [ctypes.c_int]
@@ -149,6 +155,28 @@ def fgattn_mask_emit(params, mask_indptr, mask_indices, workspace, stream=None):
     _check(lib().fgattn_mask_emit(ctypes.byref(params), mask_indptr.data_ptr(), mask_indices.data_ptr(),
                                   int(mask_indices.numel()), workspace.data_ptr(),
                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+
+GROUP_CONSECUTIVE, GROUP_XOR = 0, 1
+
+
+def fgattn_group_workspace_bytes(params, mode):
+    return int(lib().fgattn_group_workspace_bytes(ctypes.byref(params), int(mode)))
+
+
+def fgattn_group_select(mask_indptr, mask_indices, params, mode, group_tiles, union_indptr, workspace, stream=None):
+    """Query-tile grouping, first half: fills group_tiles and union_indptr (device tensors)."""
+    _check(lib().fgattn_group_select(mask_indptr.data_ptr(), mask_indices.data_ptr(), ctypes.byref(params), int(mode),
+                                     group_tiles.data_ptr(), union_indptr.data_ptr(), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+
+def fgattn_group_emit(params, mode, group_tiles, union_indptr, union_indices, union_members, workspace, stream=None):
+    """Query-tile grouping, second half: fills union_indices / union_members."""
+    _check(lib().fgattn_group_emit(ctypes.byref(params), int(mode), group_tiles.data_ptr(), union_indptr.data_ptr(),
+                                   union_indices.data_ptr(), union_members.data_ptr(), int(union_indices.numel()),
+                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                   _stream_ptr(stream)))
 
 
 def fgattn_plan(mask_indptr, params, workspace, stream=None):

@@ -62,3 +62,66 @@ def test_grouped_with_empty_members_and_repeating_patterns(oracle_mod):
         say("grouped patterns %s: union entries %d" % (mode, ui.size))
         got = run_grouped(prob, tiles, up, ui, um)
         check_against_oracle(oracle_mod, prob, got, what=w.name + " " + mode)
+
+
+def gpu_grouping(prob, mode):
+    """Runs the device pre-pass; returns (tiles [groups, R], union_indptr, union_indices, union_members) as numpy."""
+    w = prob.w
+    p = prob.params()
+    R = 128 // w.M
+    NG = (w.QB + R - 1) // R
+    groups = w.B * w.H * NG
+    m = F.GROUP_XOR if mode == "xor" else F.GROUP_CONSECUTIVE
+    ws = torch.empty(F.fgattn_group_workspace_bytes(p, m), dtype=torch.uint8, device="cuda")
+    tiles = torch.full((groups * R,), -9, dtype=torch.int32, device="cuda")
+    up = torch.full((groups + 1,), -1, dtype=torch.int64, device="cuda")
+    F.fgattn_group_select(prob.d_indptr, prob.d_indices, p, m, tiles, up, ws)
+    nnz = int(up[-1].item())
+    ui = torch.full((nnz + 8,), -7, dtype=torch.int32, device="cuda")
+    um = torch.full((nnz + 8,), 0xEE, dtype=torch.uint8, device="cuda")
+    F.fgattn_group_emit(p, m, tiles, up, ui[:nnz], um[:nnz], ws)
+    torch.cuda.synchronize()
+    assert (ui[nnz:] == -7).all() and (um[nnz:] == 0xEE).all(), "emit wrote past the capacity"
+    return tiles.cpu().numpy().reshape(groups, R), up.cpu().numpy(), ui[:nnz].cpu().numpy(), um[:nnz].cpu().numpy()
+
+
+@pytest.mark.parametrize("mode", ["consecutive", "xor"])
+@pytest.mark.parametrize("M,N,L,kind", [(32, 1, 1024, W.MASK_RANDOM), (16, 8, 1000, W.MASK_WINDOW_FILL), (64, 3, 1000, W.MASK_RANDOM),
+                                        (16, 1, 3000, W.MASK_WINDOW_FILL)])
+def test_device_grouping_equals_the_oracles(mode, M, N, L, kind):
+    grid = {1024: (4, 16, 16), 1000: (10, 10, 10), 3000: (3, 25, 40)}[L]
+    w = W.Workload("grouping-%s-M%d-N%d-L%d" % (mode, M, N, L), H=3, L=L, d=64, M=M, N=N, grid=grid, window=(1, 2, 2),
+                   kind=kind, density=0.3, seed=6200 + M + N)
+    prob = Problem(w)
+    say("device grouping %s" % w.name)
+    got = gpu_grouping(prob, mode)
+    ref = GR.grouped_mask(prob.indptr, prob.indices, w.H, w.QB, w.G, 128 // M, mode)
+    for a, b, name in zip(got, ref, ("group_tiles", "union_indptr", "union_indices", "union_members")):
+        assert np.array_equal(a, b), name
+
+
+def test_device_grouping_then_forward(oracle_mod):
+    # everything on the device: mask -> grouping -> grouped attention, against the oracle on the ungrouped mask
+    w = W.Workload("group-then-attend", H=2, L=2048, d=128, M=32, N=1, grid=(8, 16, 16), window=(1, 3, 3),
+                   kind=W.MASK_WINDOW_FILL, density=0.3, seed=6300)
+    prob = Problem(w)
+    for mode in ("xor", "consecutive"):
+        tiles, up, ui, um = gpu_grouping(prob, mode)
+        say("device grouping + forward %s: union entries %d vs %d" % (mode, ui.size, prob.indices.size))
+        got = run_grouped(prob, tiles, up, ui, um)
+        check_against_oracle(oracle_mod, prob, got, what=w.name + " " + mode)
+
+
+def test_grouping_argument_checks():
+    prob = Problem(W.TINY)
+    p = prob.params()
+    assert F.fgattn_group_workspace_bytes(p, 7) == 0
+    ws = torch.empty(F.fgattn_group_workspace_bytes(p, F.GROUP_XOR), dtype=torch.uint8, device="cuda")
+    tiles = torch.empty(prob.w.items, dtype=torch.int32, device="cuda")
+    up = torch.empty(prob.w.items // 8 + 1, dtype=torch.int64, device="cuda")
+    with pytest.raises(F.FgattnError) as e:
+        F.fgattn_group_select(prob.d_indptr, prob.d_indices, p, 7, tiles, up, ws)
+    assert e.value.code == F.E_FLAGS
+    with pytest.raises(F.FgattnError) as e:
+        F.fgattn_group_select(prob.d_indptr, prob.d_indices, p, F.GROUP_XOR, tiles, up, ws[:512])
+    assert e.value.code == F.E_WORKSPACE
