@@ -3,12 +3,16 @@
 // One persistent workgroup (4 waves) processes one work item at a time: a block of M query
 // rows of one head against the compacted list of its active keys (paper Sec. 4.1, Fig. 1b).
 // Per item: the query fragment stays in registers; the active K/V rows are gathered straight
-// from global memory into LDS tiles with per-lane-address LDS-DMA loads (the gather-load of
-// Sec. 4.1, re-designed for CDNA4), double-buffered so the gather of tile t+1 overlaps the
-// matrix work on tile t (Sec. 4.1 "Overlapped indirect key/value load latency"); bf16 MFMA
-// computes S^T = K_rel Q^T and O^T = V_rel^T P^T with fp32 online-softmax state in registers
-// (Sec. 2 "Efficient dense attention").  Work items are fetched from a device-side queue in
-// the order a pre-pass wrote (Sec. 4.2 "Load balancing", Appendix B).
+// from global memory into rings of LDS tiles with per-lane-address LDS-DMA loads (the
+// gather-load of Sec. 4.1, re-designed for CDNA4), one or two tiles ahead of their use
+// (Sec. 4.1 "Overlapped indirect key/value load latency"); bf16 MFMA computes
+// S^T = K_rel Q^T and O^T = V_rel^T P^T with fp32 online-softmax state in registers (Sec. 2
+// "Efficient dense attention").  A gather instruction holds the wave that issues it until the
+// vector-memory path has taken it (~170 clocks under load); MFMAs issued before it keep
+// executing meanwhile, so each tile's key loop interleaves one gather with one MFMA of each
+// contraction, and keeps the softmax arithmetic in a separate vector-ALU phase.  Work items are
+// fetched from a device-side queue in the order a pre-pass wrote (Sec. 4.2 "Load balancing",
+// Appendix B).
 //
 // Transposed formulation: scores are produced as S^T (keys x queries) so that, in the MFMA
 // accumulator layout, one lane owns one query column.  Row statistics (max, sum) are then
@@ -50,7 +54,7 @@ __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0
 // offset); the wave's 64 chunks land lane-linearly in LDS at lds_base + 16*lane (LDS-DMA, no
 // VGPR staging).  Written as inline assembly so that the compiler does not track the transfer:
 // the kernel orders these loads against LDS reads itself (vmcnt(0) + workgroup barrier once per
-// tile), which lets the gather of tile t+1 stay in flight during all of tile t's matrix work.
+// tile), which lets the gathers of later tiles stay in flight during all of a tile's matrix work.
 __device__ __forceinline__ void gather16_to_lds(const void* base, unsigned byte_off, unsigned lds_base) {
   // base and lds_base are wave-uniform by construction; readfirstlane pins them to scalar registers
   // (it folds away when the value already lives in one)
@@ -294,7 +298,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     // Position p = T*NT + wv*RPW + i*RPI + lrow of the compacted list is fetched by this lane with load
     // instruction i of tile T.  Pipeline per tile T (one iteration per tile, one barrier each):
     //   iteration T-3: group ids fetched          iteration T-2: ids -> key rows, K(T) gathered
-    //   iteration T-1: S(T) = K(T) Q^T, row max   iteration T  : exp -> P(T); V(T) gathered
+    //   iteration T-1: S(T) = K(T) Q^T, row max   iteration T  : V(T) gathered; P(T) = exp(S(T) - m)
     //   iteration T+1: O += V(T)^T P(T)^T
     // Past the end of the list the pipeline keeps running on the last tile again (clamped tile index): a few
     // redundant, in-bounds gathers per work item instead of existence checks in every iteration.
@@ -428,11 +432,12 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS s16x4*)(p0 + 8 * C::ROWB));
       return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // O^T += V^T P^T with V in slot `vslot` (a constant).  With GATHER, the phase also issues this iteration's
-    // gathers, one per MFMA slot: V rows of the current tile (keys in keyA) -> the V slot this phase does not
-    // read, then K rows of the tile after next (keys in keyC) -> the K slot whose tile was multiplied during the
-    // previous iteration.
-    auto pv_phase = [&](auto vslot, const i32x4 (&Pin)[2], auto with_gather, auto with_qk, f32x16& Sn) {
+    // Phase X.  O^T += V^T P^T with V in slot `vslot` (a constant) and, with QK, Sn = K Q^T with K in the same
+    // slot number of the K ring: one MFMA of each per slot.  With GATHER, every slot also issues one of this
+    // iteration's gathers: V rows of the current tile (keys in keyA) -> the V slot this phase does not read, then
+    // K rows of the tile after next (keys in keyC) -> the K slot this phase does not read.  The gather holds the
+    // wave; the two MFMAs just issued execute underneath it.
+    auto x_phase = [&](auto vslot, const i32x4 (&Pin)[2], auto with_gather, auto with_qk, f32x16& Sn) {
       constexpr bool GATHER = decltype(with_gather)::value;
       constexpr bool QK = decltype(with_qk)::value && PART != PART_GATHER;   // also Sn = K(slot vslot) Q^T
       const unsigned char* vst = smem + (2 + vslot) * C::TENSOR_BYTES;
@@ -487,11 +492,11 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         slot(std::integral_constant<int, 7>());
       }
     };
-    // Sn = K Q^T with K in slot `kslot` (tile Tm).  With EXP, the exponentials of the previous tile's scores So
-    // run on the vector ALU in the shadow of the dependent MFMA chain: P = exp2(c*(So - m)), row sum, bf16 pack
-    // into Pout.  Then the row max of the new scores and the rare decision to move the exponent base (see
-    // kLazyLog2).  Also rotates the key-row sets (t+1 -> t, t+2 -> t+1).
-    auto qk_phase = [&](auto kslot, int Tm, f32x16& Sn, const f32x16& So, i32x4 (&Pout)[2], auto with_exp,
+    // Phase Y, vector ALU only in the key loop.  With EXP: P = exp2(c*(So - m)) of the previous tile's scores So,
+    // row sum, bf16 pack into Pout.  Then the row max of the new scores Sn (tile Tm) and the rare decision to
+    // move the exponent base (see kLazyLog2).  Also rotates the key-row sets (t+1 -> t, t+2 -> t+1).  With MFMA
+    // (prologue only) it first computes Sn = K Q^T with K in slot `kslot`.
+    auto y_phase = [&](auto kslot, int Tm, f32x16& Sn, const f32x16& So, i32x4 (&Pout)[2], auto with_exp,
                         auto with_mfma) {
       constexpr bool EXP = decltype(with_exp)::value;
       constexpr bool MFMA = decltype(with_mfma)::value;
@@ -535,13 +540,13 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
             psum1 += p1;
             f32x2 pp = {p0, p1};
             int pk = __builtin_bit_cast(int, __builtin_convertvector(pp, bf16x2));
-            // the packed pair is consumed only after the next barrier; without this pin the compiler sinks the
-            // whole exponential block out of the MFMA shadow to the end of the phase
+            // the packed pair is consumed only after the next barrier; the pin keeps the compiler from sinking the
+            // exponentials there, into the phase whose issue slots belong to the gathers
             asm volatile("" : "+v"(pk));
             Pout[r >> 3][(r & 7) >> 1] = pk;
           }
         }
-        __builtin_amdgcn_sched_barrier(0);   // keep one MFMA + its share of the exponentials per slot
+        __builtin_amdgcn_sched_barrier(0);
       };
       slot(std::integral_constant<int, 0>());
       slot(std::integral_constant<int, 1>());
@@ -571,11 +576,10 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
     // Iteration t, PAR = t & 1 (a constant, so every LDS slot is an immediate):
-    //   X: O += V(t-1)^T P(t-1)^T (V slot PAR^1)  ||  gathers V(t) -> V slot PAR and K(t+2) -> K slot PAR (each
-    //      gather instruction holds the issuing wave for the time its 1 KiB takes through the vector-memory path;
-    //      the MFMAs run underneath)
-    //   Y: S(t+1) = K(t+1) Q^T (K slot PAR^1)  ||  P(t) = exp(S(t)) on the vector ALU; then the row max of S(t+1)
-    // Every gathered tile thus has a full iteration to arrive before the barrier that publishes it.
+    //   X: O += V(t-1)^T P(t-1)^T (V slot PAR^1)  ||  S(t+1) = K(t+1) Q^T (K slot PAR^1)  ||  gathers V(t) -> V slot
+    //      PAR and K(t+2) -> K slot PAR
+    //   Y: P(t) = exp(S(t) - m) and the row max of S(t+1), on the vector ALU
+    // Every gathered tile thus has phase Y and the barrier's wait to arrive before it is published.
     auto iteration = [&](int t, auto parc, const i32x4 (&Pin)[2], i32x4 (&Pout)[2], f32x16& Sn, const f32x16& So) {
       constexpr int PAR = decltype(parc)::value;
       // K(t+1) and V(t-1), gathered during the previous iteration, become visible to every wave; every wave is
@@ -590,14 +594,14 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       }
       make_keys(min(t + 2, last));        // ids fetched during the previous iteration -> keyC
       fetch_ids(min(t + 3, last));
-      pv_phase(std::integral_constant<int, PAR ^ 1>(), Pin, yes(), yes(), Sn);
+      x_phase(std::integral_constant<int, PAR ^ 1>(), Pin, yes(), yes(), Sn);
       if (__builtin_expect(resc, 0)) {
 #pragma unroll
         for (int db = 0; db < C::DBLK; db++)
 #pragma unroll
           for (int r = 0; r < 16; r++) O[db][r] *= alpha;
       }
-      qk_phase(std::integral_constant<int, PAR ^ 1>(), min(t + 1, last), Sn, So, Pout, yes(), no());
+      y_phase(std::integral_constant<int, PAR ^ 1>(), min(t + 1, last), Sn, So, Pout, yes(), no());
     };
 
     if (ntiles > 0) {
@@ -646,7 +650,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       wait_vmem_all();
       __syncthreads();
       // S(0) from K slot 0; keyA/keyB end up as keys(0)/keys(1)
-      qk_phase(std::integral_constant<int, 0>(), 0, SA, SA, PA, no(), yes());
+      y_phase(std::integral_constant<int, 0>(), 0, SA, SA, PA, no(), yes());
       m_run = m_pend;   // O = 0 and l = 0 so far: the first exponent base needs no rescale
       resc = false;
       int t = 0;
@@ -657,8 +661,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       if (t < ntiles) iteration(t, std::integral_constant<int, 0>(), PB, PA, SB, SA);
       wait_vmem_all();
       __syncthreads();
-      if ((ntiles & 1) == 0) pv_phase(std::integral_constant<int, 1>(), PB, no(), no(), SA);
-      else pv_phase(std::integral_constant<int, 0>(), PA, no(), no(), SA);
+      if ((ntiles & 1) == 0) x_phase(std::integral_constant<int, 1>(), PB, no(), no(), SA);
+      else x_phase(std::integral_constant<int, 0>(), PA, no(), no(), SA);
     }
 
     // ---------------- epilogue ----------------
