@@ -15,7 +15,8 @@ namespace fg {
 // the length of its key/value list; items are handed out longest first.  Here the order is
 // built per head -- all workgroups drain one head before the next, so concurrently running
 // items share that head's K/V in cache -- and longest-first inside a head.
-// One workgroup per (batch, head) slice.  workspace layout: int32 ctrl[64] (ctrl[0] queue head,
+// blockIdx.x = (batch, head) slice; blockIdx.y splits the slice's query blocks when they are ranked exactly.
+// workspace layout: int32 ctrl[64] (ctrl[0] queue head,
 // ctrl[1] finished-workgroup count), then int32 order[n_items].
 // ------------------------------------------------------------------------------------------
 constexpr int kPlanThreads = 256;
@@ -29,9 +30,10 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(const int64_t* indpt
   __shared__ int s_max;
   const int tid = threadIdx.x;
   const int64_t base = (int64_t)blockIdx.x * QB;
-  if (blockIdx.x == 0 && tid < 2) ctrl[tid] = 0;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && tid < 2) ctrl[tid] = 0;
   if (!sorted || indptr == nullptr) {
-    for (int j = tid; j < QB; j += kPlanThreads) order[base + j] = (int32_t)(base + j);
+    if (blockIdx.y == 0)
+      for (int j = tid; j < QB; j += kPlanThreads) order[base + j] = (int32_t)(base + j);
     return;
   }
   auto cost_of = [&](int j) -> int {
@@ -39,19 +41,25 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(const int64_t* indpt
     return c > 0x7fffffff ? 0x7fffffff : (c < 0 ? 0 : (int)c);
   };
   if (QB <= kRankMax) {
+    // exact rank by counting; blockIdx.y splits the query blocks of the slice, four lanes share one block's count
     for (int j = tid; j < QB; j += kPlanThreads) s_cost[j] = cost_of(j);
     __syncthreads();
-    for (int j = tid; j < QB; j += kPlanThreads) {
-      const int c = s_cost[j];
+    const int part = tid & 3;
+    for (int j0 = blockIdx.y * (kPlanThreads / 4); j0 < QB; j0 += gridDim.y * (kPlanThreads / 4)) {
+      const int j = j0 + (tid >> 2);
+      const int c = j < QB ? s_cost[j] : 0;
       int rank = 0;
-      for (int i = 0; i < QB; i++) {
+      for (int i = part; i < QB; i += 4) {
         const int ci = s_cost[i];
         rank += (ci > c) || (ci == c && i < j);
       }
-      order[base + rank] = (int32_t)(base + j);
+      rank += __shfl_xor(rank, 1);
+      rank += __shfl_xor(rank, 2);
+      if (part == 0 && j < QB) order[base + rank] = (int32_t)(base + j);
     }
     return;
   }
+  if (blockIdx.y != 0) return;
   // bucket path: descending buckets over [0, max cost]
   if (tid == 0) s_max = 1;
   for (int i = tid; i < kBuckets; i += kPlanThreads) s_hist[i] = 0;
@@ -186,7 +194,9 @@ static int run_plan(const int64_t* indptr, const fgattn_params* p, void* workspa
   int32_t* order = ctrl + 64;
   if (QB == 0) QB = (p->L + p->M - 1) / p->M;
   const int sorted = (p->flags & (FGATTN_FLAG_STATIC_ASSIGN | FGATTN_FLAG_FIFO_QUEUE)) ? 0 : 1;
-  hipLaunchKernelGGL(plan_kernel, dim3(p->B * p->H), dim3(kPlanThreads), 0, stream, indptr, ctrl, order, QB, sorted);
+  const int splits = QB <= kRankMax ? (QB + kPlanThreads / 4 - 1) / (kPlanThreads / 4) : 1;   // 64 query blocks per workgroup
+  hipLaunchKernelGGL(plan_kernel, dim3(p->B * p->H, splits < 64 ? splits : 64), dim3(kPlanThreads), 0, stream, indptr, ctrl,
+                     order, QB, sorted);
   return hipGetLastError() == hipSuccess ? FGATTN_OK : FGATTN_E_DEVICE;
 }
 
