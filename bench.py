@@ -177,7 +177,10 @@ def main():
         ms_emit = time_calls(lambda: F.fgattn_mask_emit(pm, m_indptr, m_indices, mws), 2, 5)
         res["mask"] = {"top_p": 0.9, "select_ms": ms_select, "emit_ms": ms_emit, "density": m_nnz / float(w.items * w.G),
                        "workspace_MB": mws.numel() / 1e6,
-                       "algorithmic_GB": (3 * w.items * w.G * 4.0 + 4.0 * m_nnz + 2.0 * w.H * w.L * w.d * 2) / 1e9,
+                       # scores written once and read once (the row of a query block then stays in LDS), one bit
+                       # per score written and read, the ids written, Q and K read
+                       "algorithmic_GB": (2 * w.items * w.G * 4.0 + 2 * w.items * w.G / 8.0 + 4.0 * m_nnz +
+                                          2.0 * w.H * w.L * w.d * 2) / 1e9,
                        "data": "N(0,1) + random Fourier features of the token grid position (gain 2.5)"}
         del dmq, dmk, mws, m_indices
     if not args.no_dense:

@@ -48,8 +48,12 @@ enum {
    * ordered by decreasing active-list length and fetched from a device-side queue. */
   FGATTN_FLAG_STATIC_ASSIGN = 1,  /* ablation "no scheduler": item j goes to workgroup j mod grid, natural order */
   FGATTN_FLAG_FIFO_QUEUE = 2,     /* device-side queue, but natural order (no longest-first ordering) */
-  FGATTN_FLAG_REUSE_PLAN = 4      /* skip the ordering pre-pass: `workspace` already holds the order built by an
+  FGATTN_FLAG_REUSE_PLAN = 4,     /* skip the ordering pre-pass: `workspace` already holds the order built by an
                                      earlier fgattn_forward/fgattn_plan call for the same mask and params */
+  /* Read by the fgattn_mask_* calls only (the others ignore it): select from the rows of scores in device
+   * memory even where a row fits in LDS (at most 32768 key blocks), the path that longer rows always take.
+   * Same results; it changes the workspace size, so pass the same flags to all three mask calls. */
+  FGATTN_FLAG_MASK_ROWS_IN_HBM = 8
 };
 
 typedef struct fgattn_params {
@@ -170,7 +174,8 @@ int fgattn_validate_mask(const int64_t* mask_indptr, const int32_t* mask_indices
  * fgattn_mask_select: q, k as in fgattn_forward (strides from `p`; v/out strides ignored).  Writes
  *   mask_indptr (device, int64 [B*H*ceil(L/M) + 1]) and keeps the per-block cut in `workspace`
  *   (device, 256-byte aligned, at least fgattn_mask_workspace_bytes(p): block means, one fp32 score per
- *   (query block, key block), 20 bytes per query block).  top_p must be in (0, 1] (FGATTN_E_SCALE otherwise).
+ *   (query block, key block), 20 bytes per query block, and one bit per (query block, key block) where
+ *   a row of scores fits in LDS).  top_p must be in (0, 1] (FGATTN_E_SCALE otherwise).
  * fgattn_mask_emit: after the caller has read nnz = mask_indptr[last] and provided mask_indices (device, int32,
  *   capacity >= nnz entries): writes the kept key-block ids of every query block in ascending order.  Entries
  *   that would fall beyond `indices_capacity` are dropped, never written out of bounds.  `workspace` must be the

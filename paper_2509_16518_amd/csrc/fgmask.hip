@@ -4,12 +4,15 @@
 // mass reaches p -- written straight into the CSR form the forward kernel reads.
 //
 // Kernels (all on the caller's stream):
-//   pool_kernel     block means (fp32 running sum in row order, fp32 divide, one bf16 rounding)
-//   scores_kernel   S = scale * Q_avg K_avg^T with bf16 MFMA, fp32 scores to the workspace
-//   select_kernel   one workgroup per query block: finds the CUT, the 64-bit key (score, then
-//                   lower id first) of the last kept key block, without sorting the row
-//   scan_kernel     counts -> indptr
-//   emit_kernel     ids whose key is >= the cut, ascending, into indices
+//   pool_kernel        block means (fp32 running sum in row order, fp32 divide, one bf16 rounding)
+//   scores_kernel      S = scale * Q_avg K_avg^T with bf16 MFMA, fp32 scores to the workspace
+//   select_lds_kernel  rows of up to 32768 scores: persistent workgroups, the row of a query block held in
+//                      LDS; finds the CUT, the 64-bit key (score, then lower id first) of the last kept key
+//                      block, without sorting the row, and leaves the kept set as one bit per key block
+//   select_kernel      longer rows (or on request): the same selection, one workgroup per query block,
+//                      every pass reading the row from device memory; leaves only the cut
+//   scan_kernel        counts -> indptr
+//   emit_bits_kernel / emit_kernel   kept ids, ascending, into indices (from the bit rows / from scores and cut)
 //
 // Selection works on integers so that it does not depend on the order of additions: the weight
 // of a key block is exp2((s - max) * log2 e) in 2^-40 fixed point, the row's mass Z is the integer
@@ -32,6 +35,11 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 constexpr int kSelThreads = 256;
 constexpr int kBins = 2048;
 constexpr int kCap = 2048;          // members of the crossing bin that are sorted in LDS
+// Rows of up to kRowLdsFloats scores are selected by a 1024-thread workgroup that keeps the row in LDS.
+constexpr int kRowThreads = 1024;
+constexpr int kRowBins = 2048;
+constexpr int kRowCap = 1024;
+constexpr int kRowLdsFloats = 32768;
 constexpr float kLog2e = 1.44269504088896340736f;
 
 __device__ __forceinline__ unsigned ordered_bits(float s) {   // monotone: larger score, larger unsigned
@@ -43,13 +51,20 @@ __device__ __forceinline__ float from_ordered(unsigned o) {
   return __uint_as_float(u);
 }
 // ---------------------------------------------------------------------------------------------
-// Step 1: block means.  One thread per (block, column): the additions run in row order, so every
-// implementation of this reading produces the same bits.
+// Step 1: block means.  One thread per (block, pair of columns): the additions of a column run in
+// row order, so every implementation of this reading produces the same bits.
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(128) pool_kernel(const uint16_t* x, int64_t sb, int64_t sh, int64_t sl, int H, int L,
-                                                    int d, int rows_per_block, int nblocks, uint16_t* pooled,
-                                                    unsigned* range_init) {
-  const int c = threadIdx.x;
+__device__ __forceinline__ uint16_t mean_bf16(float acc, int n) {
+  const float mean = __fdiv_rn(acc, (float)n);
+  unsigned u = __float_as_uint(mean);
+  u += 0x7FFFu + ((u >> 16) & 1u);   // nearest even; the inputs are finite
+  return (uint16_t)(u >> 16);
+}
+
+__global__ void __launch_bounds__(64) pool_kernel(const uint16_t* x, int64_t sb, int64_t sh, int64_t sl, int H, int L,
+                                                   int d, int rows_per_block, int nblocks, uint16_t* pooled,
+                                                   unsigned* range_init) {
+  const int c = threadIdx.x * 2;
   const int blk = blockIdx.x;
   const int slice = blockIdx.y;
   if (c >= d) return;
@@ -61,34 +76,56 @@ __global__ void __launch_bounds__(128) pool_kernel(const uint16_t* x, int64_t sb
   const int b = slice / H, h = slice - b * H;
   const int r0 = blk * rows_per_block;
   const int r1 = min(r0 + rows_per_block, L);
-  const uint16_t* p = x + b * sb + h * sh + (int64_t)r0 * sl + c;
-  float acc = 0.0f;
-  for (int r = r0; r < r1; r++, p += sl) acc = acc + __uint_as_float((unsigned)(*p) << 16);
-  const float mean = __fdiv_rn(acc, (float)(r1 - r0));
-  unsigned u = __float_as_uint(mean);
-  u += 0x7FFFu + ((u >> 16) & 1u);   // nearest even; the inputs are finite
-  pooled[((int64_t)slice * nblocks + blk) * d + c] = (uint16_t)(u >> 16);
+  const uint16_t* p = x + b * sb + h * sh + (int64_t)r0 * sl + c;   // 4-byte aligned: strides are multiples of 8 elements
+  float acc0 = 0.0f, acc1 = 0.0f;
+  int r = r0;
+  for (; r + 8 <= r1; r += 8, p += 8 * sl) {
+    unsigned w[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) w[i] = *reinterpret_cast<const unsigned*>(p + i * sl);
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      acc0 = acc0 + __uint_as_float(w[i] << 16);
+      acc1 = acc1 + __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+  }
+  for (; r < r1; r++, p += sl) {
+    const unsigned w = *reinterpret_cast<const unsigned*>(p);
+    acc0 = acc0 + __uint_as_float(w << 16);
+    acc1 = acc1 + __uint_as_float(w & 0xFFFF0000u);
+  }
+  const unsigned out = (unsigned)mean_bf16(acc0, r1 - r0) | ((unsigned)mean_bf16(acc1, r1 - r0) << 16);
+  *reinterpret_cast<unsigned*>(pooled + ((int64_t)slice * nblocks + blk) * d + c) = out;
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 2a: scores.  A wave owns 32 query blocks (A operand, kept in registers) and walks over
-// tiles of 32 key blocks (B operand, read straight from global memory: 16 bytes per lane and
-// step); in the accumulator a register holds one query block and 32 consecutive key blocks across
-// lanes, so every store covers whole 128-byte lines.
+// Step 2a: scores.  A workgroup owns 128 query blocks (32 per wave, A operand, kept in registers)
+// and walks over tiles of 32 key blocks.  A tile is read from global memory once per workgroup,
+// whole rows at a time (16 bytes per thread, next tile in flight during this tile's MFMAs), and
+// passed through LDS, from where every wave takes it as its B operand; the 16-byte chunks of a row
+// are XOR-swizzled so that both the row-wise writes and the column-wise operand reads are free of
+// bank conflicts.  In the accumulator a register holds one query block and 32 consecutive key
+// blocks across lanes, so every store covers whole 128-byte lines.
 // ---------------------------------------------------------------------------------------------
-constexpr int kTilesPerWave = 16;
+constexpr int kTilesPerGroup = 16;
 
 template <int D>
 __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const uint16_t* kp, int64_t k_slice_stride,
                                                       int64_t k_row_stride, int QB, int G, int Gs, float scale,
                                                       float* scores, unsigned* range) {
   constexpr int STEPS = D / 16;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  constexpr int ROWB = D * 2;                 // bytes of a row of K
+  constexpr int CHUNKS = ROWB / 16;           // 16-byte chunks per row
+  constexpr int TILEB = 32 * ROWB;
+  constexpr int LPT = TILEB / 16 / 256;       // chunks per thread and tile
+  static_assert(LPT >= 1, "a tile is at least one chunk per thread");
+  __shared__ __attribute__((aligned(16))) unsigned char ktile[2][TILEB];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int ln = lane & 31, g = lane >> 5;
   const int slice = blockIdx.z;
-  const int q0 = blockIdx.y * 32;
-  const int tile0 = (blockIdx.x * 4 + wv) * kTilesPerWave;
-  if (tile0 * 32 >= G) return;
+  const int q0 = blockIdx.y * 128 + wv * 32;   // (a wave past the last query block still helps with the tiles)
+  const int tile0 = blockIdx.x * kTilesPerGroup;
+  auto swz = [](int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
   bf16x8 qf[STEPS];
   {
     const int qrow = min(q0 + ln, QB - 1);
@@ -97,11 +134,21 @@ __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const u
     for (int s = 0; s < STEPS; s++) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(src + (2 * s + g) * 16));
   }
   const char* kbase = reinterpret_cast<const char*>(kp + slice * k_slice_stride);
-  auto load_tile = [&](int tile, bf16x8 (&kf)[STEPS]) {
-    const int krow = min(tile * 32 + ln, G - 1);
-    const char* src = kbase + (int64_t)krow * k_row_stride * 2;
+  i32x4 stage[LPT];
+  auto fetch_tile = [&](int tile) {
 #pragma unroll
-    for (int s = 0; s < STEPS; s++) kf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(src + (2 * s + g) * 16));
+    for (int i = 0; i < LPT; i++) {
+      const int ci = i * 256 + tid, row = ci / CHUNKS, c = ci % CHUNKS;
+      const int krow = min(tile * 32 + row, G - 1);
+      stage[i] = *reinterpret_cast<const i32x4*>(kbase + (int64_t)krow * k_row_stride * 2 + c * 16);
+    }
+  };
+  auto stash_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < LPT; i++) {
+      const int ci = i * 256 + tid, row = ci / CHUNKS, c = ci % CHUNKS;
+      *reinterpret_cast<i32x4*>(&ktile[buf][row * ROWB + ((c ^ swz(row)) * 16)]) = stage[i];
+    }
   };
   // running range of the scores this lane produced, per accumulator register (= per query block)
   float vmax[16], vmin[16];
@@ -110,16 +157,21 @@ __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const u
     vmax[r] = -INFINITY;
     vmin[r] = INFINITY;
   }
-  const int ntiles = min(kTilesPerWave, (G - tile0 * 32 + 31) / 32);
-  bf16x8 kf[STEPS], kn[STEPS];
-  load_tile(tile0, kf);
+  const int ntiles = min(kTilesPerGroup, (G - tile0 * 32 + 31) / 32);   // >= 1 by the grid
+  fetch_tile(tile0);
+  stash_tile(0);
+  __syncthreads();
   for (int t = 0; t < ntiles; t++) {
-    if (t + 1 < ntiles) load_tile(tile0 + t + 1, kn);   // next tile's operand in flight during this tile's MFMAs
+    if (t + 1 < ntiles) fetch_tile(tile0 + t + 1);
+    const unsigned char* kt = ktile[t & 1];
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[r] = 0.0f;
 #pragma unroll
-    for (int s = 0; s < STEPS; s++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[s], acc, 0, 0, 0);
+    for (int s = 0; s < STEPS; s++) {
+      const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kt + ln * ROWB + (((2 * s + g) ^ swz(ln)) * 16)));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf, acc, 0, 0, 0);
+    }
     const int col = (tile0 + t) * 32 + ln;
     if (col < G) {
 #pragma unroll
@@ -131,8 +183,8 @@ __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const u
         if (qrow < QB) scores[((int64_t)slice * QB + qrow) * Gs + col] = v;
       }
     }
-#pragma unroll
-    for (int s = 0; s < STEPS; s++) kf[s] = kn[s];
+    if (t + 1 < ntiles) stash_tile((t + 1) & 1);   // (the buffer that was read in step t - 1, before the last barrier)
+    __syncthreads();
   }
   // one (max, min) update per query block and wave: reduce over the 32 lanes that share the block
 #pragma unroll
@@ -159,38 +211,51 @@ __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const u
 __device__ __forceinline__ unsigned long long rank_key(float s, int j) {
   return ((unsigned long long)ordered_bits(s) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)j);
 }
+// Weight of a score relative to the row maximum: trunc(2^40 * 2^((s - rmax) * log2 e)), 2^-40 fixed point.
+// The bare exponential instruction differs from exp2f only below 2^-126, where the weight is zero either way.
+// The product with 2^40 is exact, and so is its split into a multiple of 2^16 and a remainder (the hardware
+// has no float -> 64-bit integer conversion).
 __device__ __forceinline__ unsigned long long weight_of(float s, float rmax) {
-  const float e = exp2f((s - rmax) * kLog2e);          // in (0, 1]
-  return (unsigned long long)(e * 1099511627776.0f);   // 2^40 fixed point, truncated
+  const float x = __builtin_amdgcn_exp2f((s - rmax) * kLog2e) * 1099511627776.0f;   // in [0, 2^40]
+  const unsigned hi = (unsigned)(x * (1.0f / 65536.0f));
+  const unsigned lo = (unsigned)__builtin_fmaf(-(float)hi, 65536.0f, x);
+  return ((unsigned long long)hi << 16) + lo;
 }
 
 // Visits every score of a row: four consecutive scores per thread and step (16-byte loads; rows start 16-byte
 // aligned and their stride is a multiple of four floats), four steps in flight.
-template <typename Fn>
+template <int THREADS, typename Fn>
 __device__ __forceinline__ void for_each_score(const float* s, int G, Fn&& fn) {
-  constexpr int STEP = kSelThreads * 4;
-  auto visit = [&](const float4& v, int j4) {
+  constexpr int STEP = THREADS * 4;
+  auto whole = [&](const float4& v, int j4) {
+    fn(v.x, j4);
+    fn(v.y, j4 + 1);
+    fn(v.z, j4 + 2);
+    fn(v.w, j4 + 3);
+  };
+  auto ragged = [&](const float4& v, int j4) {
     fn(v.x, j4);
     if (j4 + 1 < G) fn(v.y, j4 + 1);
     if (j4 + 2 < G) fn(v.z, j4 + 2);
     if (j4 + 3 < G) fn(v.w, j4 + 3);
   };
   int j4 = threadIdx.x * 4;
-  for (; j4 + 3 * STEP < G; j4 += 4 * STEP) {
+  for (; j4 + 3 * STEP + 3 < G; j4 += 4 * STEP) {
     const float4 a = *reinterpret_cast<const float4*>(s + j4);
     const float4 b = *reinterpret_cast<const float4*>(s + j4 + STEP);
     const float4 c = *reinterpret_cast<const float4*>(s + j4 + 2 * STEP);
     const float4 d = *reinterpret_cast<const float4*>(s + j4 + 3 * STEP);
-    visit(a, j4);
-    visit(b, j4 + STEP);
-    visit(c, j4 + 2 * STEP);
-    visit(d, j4 + 3 * STEP);
+    whole(a, j4);
+    whole(b, j4 + STEP);
+    whole(c, j4 + 2 * STEP);
+    whole(d, j4 + 3 * STEP);
   }
-  for (; j4 < G; j4 += STEP) visit(*reinterpret_cast<const float4*>(s + j4), j4);
+  for (; j4 < G; j4 += STEP) ragged(*reinterpret_cast<const float4*>(s + j4), j4);
 }
 
 // Exclusive prefix of `n` over the threads of the workgroup in thread order; *total gets the sum.
-// wave_tot: four words of shared memory.  Contains two barriers.
+// wave_tot: THREADS / 64 words of shared memory.  Contains two barriers.
+template <int THREADS>
 __device__ __forceinline__ unsigned block_exclusive(unsigned n, unsigned* wave_tot, unsigned* total) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   unsigned incl = n;
@@ -202,111 +267,251 @@ __device__ __forceinline__ unsigned block_exclusive(unsigned n, unsigned* wave_t
   __syncthreads();
   unsigned before = 0;
   for (int w2 = 0; w2 < wv; w2++) before += wave_tot[w2];
-  *total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+  unsigned all = 0;
+  for (int w2 = 0; w2 < THREADS / 64; w2++) all += wave_tot[w2];
+  *total = all;
   __syncthreads();
   return before + incl - n;
 }
 
+// WITH_CNT: the histogram also counts the members of every bin.  Without, the counts are taken by a pass of
+// their own after the bin is known (one LDS atomic per score fewer; only worth it where re-reading the row is cheap).
+template <int THREADS, int BINS, int CAP, bool WITH_CNT>
 struct SelShared {
-  unsigned long long mass[kBins];
-  unsigned cnt[kBins];
-  unsigned long long cand[kCap];
-  unsigned long long red64[kSelThreads];
+  unsigned long long mass[BINS];
+  unsigned cnt[WITH_CNT ? BINS : THREADS / 64];
+  unsigned long long cand[CAP];
+  unsigned long long wave_m[THREADS / 64];
+  unsigned wave_n[THREADS / 64];
   unsigned long long mass_above, target, cut;
   unsigned n_above, bin, bin_cnt, ncand, klo, khi, run;
   int done;
 };
 
-__device__ __forceinline__ unsigned long long block_sum_u64(SelShared& sh, unsigned long long v) {
-  const int tid = threadIdx.x;
-  sh.red64[tid] = v;
+template <int THREADS, int BINS, int CAP, bool WITH_CNT>
+__device__ __forceinline__ unsigned long long block_sum_u64(SelShared<THREADS, BINS, CAP, WITH_CNT>& sh, unsigned long long v) {
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  if ((threadIdx.x & 63) == 0) sh.wave_m[threadIdx.x >> 6] = v;
   __syncthreads();
-  for (int off = kSelThreads / 2; off > 0; off >>= 1) {
-    if (tid < off) sh.red64[tid] += sh.red64[tid + off];
-    __syncthreads();
-  }
-  const unsigned long long r = sh.red64[0];
+  unsigned long long r = 0;
+  for (int w2 = 0; w2 < THREADS / 64; w2++) r += sh.wave_m[w2];
   __syncthreads();
   return r;
 }
 
-// Finds, in the histogram just built, the bin where the running mass (starting from mass_above) reaches the
-// target; updates mass_above / n_above to exclude that bin and stores bin / bin_cnt.
-__device__ __forceinline__ void locate_bin(SelShared& sh) {
-  const int tid = threadIdx.x;
-  constexpr int PER = kBins / kSelThreads;
-  unsigned long long local = 0;
-  for (int i = 0; i < PER; i++) local += sh.mass[tid * PER + i];
-  sh.red64[tid] = local;
+// Exclusive prefixes, in thread order, of a mass and a count; *tm gets the mass of all threads.  Contains two barriers.
+template <int THREADS, int BINS, int CAP, bool WITH_CNT>
+__device__ __forceinline__ void block_exclusive_mass(SelShared<THREADS, BINS, CAP, WITH_CNT>& sh, unsigned long long m, unsigned n,
+                                                     unsigned long long* em, unsigned* en, unsigned long long* tm) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  unsigned long long im = m;
+  unsigned in = n;
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned long long um = __shfl_up(im, off);
+    const unsigned un = __shfl_up(in, off);
+    if (lane >= off) {
+      im += um;
+      in += un;
+    }
+  }
+  if (lane == 63) {
+    sh.wave_m[wv] = im;
+    sh.wave_n[wv] = in;
+  }
   __syncthreads();
-  if (tid == 0) {
-    // the caller guarantees mass_above < target <= mass_above + (mass of this histogram)
-    unsigned long long run = sh.mass_above;
-    int t = 0;
-    while (t < kSelThreads - 1 && run + sh.red64[t] < sh.target) run += sh.red64[t++];
-    int b = t * PER;
-    while (b < kBins - 1 && run + sh.mass[b] < sh.target) run += sh.mass[b++];
-    unsigned n = sh.n_above;
-    for (int i = 0; i < b; i++) n += sh.cnt[i];
+  unsigned long long bm = 0;
+  unsigned bn = 0;
+  for (int w2 = 0; w2 < wv; w2++) {
+    bm += sh.wave_m[w2];
+    bn += sh.wave_n[w2];
+  }
+  unsigned long long all = bm;
+  for (int w2 = wv; w2 < THREADS / 64; w2++) all += sh.wave_m[w2];
+  *tm = all;
+  __syncthreads();
+  *em = bm + im - m;
+  *en = bn + in - n;
+}
+
+// Finds, in the histogram just built, the bin where the running mass (starting from mass_above) reaches the
+// target; updates mass_above / n_above to exclude that bin and stores bin / bin_cnt (n_above and bin_cnt only
+// WITH_CNT).  Every thread owns BINS / THREADS consecutive bins; a prefix over the threads names the one owner
+// whose bins contain the crossing.  FIRST: the histogram is that of the whole row; its mass Z sets the target
+// ceil(top_p * Z) (at least 1, at most Z), and nothing lies above it yet.
+template <bool FIRST, int THREADS, int BINS, int CAP, bool WITH_CNT>
+__device__ __forceinline__ void locate_bin(SelShared<THREADS, BINS, CAP, WITH_CNT>& sh, float top_p) {
+  const int tid = threadIdx.x;
+  constexpr int PER = BINS / THREADS;
+  const unsigned long long base = FIRST ? 0ull : sh.mass_above;
+  unsigned long long target = FIRST ? 0ull : sh.target;
+  const unsigned n_base = FIRST ? 0u : sh.n_above;
+  unsigned long long local = 0;
+  unsigned nlocal = 0;
+  for (int i = 0; i < PER; i++) {
+    local += sh.mass[tid * PER + i];
+    if constexpr (WITH_CNT) nlocal += sh.cnt[tid * PER + i];
+  }
+  unsigned long long em, Z;
+  unsigned en;
+  block_exclusive_mass(sh, local, nlocal, &em, &en, &Z);
+  if constexpr (FIRST) {   // every thread computes the same target
+    const double t = ceil((double)top_p * (double)Z);
+    target = t < 1.0 ? 1ull : (unsigned long long)t;
+    if (target > Z) target = Z;
+  }
+  // the caller guarantees base < target <= base + (mass of this histogram); the two extra clauses only make sure
+  // that some bin is named if that did not hold
+  const unsigned long long lo = base + em;
+  const bool mine = (lo < target && (target <= lo + local || tid == THREADS - 1)) || (tid == 0 && target <= lo);
+  if (mine) {
+    unsigned long long run = lo;
+    unsigned n = n_base + en;
+    int b = tid * PER;
+    while (b < tid * PER + PER - 1 && run + sh.mass[b] < target) {
+      run += sh.mass[b];
+      if constexpr (WITH_CNT) n += sh.cnt[b];
+      b++;
+    }
     sh.mass_above = run;
-    sh.n_above = n;
     sh.bin = (unsigned)b;
-    sh.bin_cnt = sh.cnt[b];
+    if constexpr (FIRST) {
+      sh.target = target;
+      sh.n_above = 0;
+    }
+    if constexpr (WITH_CNT) {
+      sh.n_above = n;
+      sh.bin_cnt = sh.cnt[b];
+    }
   }
   __syncthreads();
 }
 
-__global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores, const unsigned* range, int G, int Gs,
-                                                             float top_p, unsigned long long* cut, unsigned* count) {
-  __shared__ SelShared sh;
+// Sorts cand[0 .. n2) (n2 a power of two, unused entries zero) by descending key.  Up to 64 keys: one wave, in
+// registers; more: the whole workgroup, in LDS.  All threads call it; it ends with a barrier.
+template <int THREADS, typename SH>
+__device__ __forceinline__ void sort_candidates(SH& sh, int n2) {
   const int tid = threadIdx.x;
-  const int64_t row = blockIdx.x;
-  const float* s = scores + row * Gs;
+  if (n2 <= 64) {
+    if (tid < 64) {
+      unsigned long long x = tid < n2 ? sh.cand[tid] : 0ull;
+      for (int k = 2; k <= 64; k <<= 1)
+        for (int jj = k >> 1; jj > 0; jj >>= 1) {
+          const unsigned long long y = __shfl_xor(x, jj);
+          const bool keep_max = ((tid & jj) == 0) == ((tid & k) == 0);   // lower lane of a descending pair, or upper of an ascending
+          x = keep_max ? (x > y ? x : y) : (x < y ? x : y);
+        }
+      if (tid < n2) sh.cand[tid] = x;   // zeros rank last, so the first n2 lanes hold what was there, sorted
+    }
+    __syncthreads();
+    return;
+  }
+  for (int k = 2; k <= n2; k <<= 1)
+    for (int jj = k >> 1; jj > 0; jj >>= 1) {
+      for (int i = tid; i < n2; i += THREADS) {
+        const int l = i ^ jj;
+        if (l > i) {
+          const unsigned long long a = sh.cand[i], b = sh.cand[l];
+          const bool desc = (i & k) == 0;
+          if (desc ? (a < b) : (a > b)) {
+            sh.cand[i] = b;
+            sh.cand[l] = a;
+          }
+        }
+      }
+      __syncthreads();
+    }
+}
 
-  // range of the scores (collected by the scores kernel)
-  const float rmax = from_ordered(range[2 * row]), rmin = from_ordered(range[2 * row + 1]);
+// Selection for one query block (row of scores `s`, in device memory or in LDS); called by all threads of the
+// workgroup.  ROW_IN_LDS: also writes the kept set as one bit per key block (`keep_bits`, Gw words per row).
+template <int THREADS, int BINS, int CAP, bool ROW_IN_LDS, typename SH>
+__device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, float rmax, float rmin, int G, float top_p,
+                                           unsigned long long* cut, unsigned* count, uint32_t* keep_bits, int Gw) {
+  constexpr bool WITH_CNT = !ROW_IN_LDS;
+  const int tid = threadIdx.x;
+  // ROW_IN_LDS, at the end (all threads; the cut is in sh.cut): one bit per key block, set where its rank key is
+  // not below the cut.  A thread ranks four consecutive key blocks, eight lanes make a word.
+  auto write_bits = [&]() {
+    if constexpr (ROW_IN_LDS) {
+      __syncthreads();
+      const unsigned long long c = sh.cut;
+      for (int base = 0; base < Gw * 32; base += THREADS * 4) {
+        const int j4 = base + tid * 4;
+        unsigned nib = 0;
+        if (j4 < G) {
+          const float4 v = *reinterpret_cast<const float4*>(s + j4);
+          nib = (rank_key(v.x, j4) >= c ? 1u : 0u) | (j4 + 1 < G && rank_key(v.y, j4 + 1) >= c ? 2u : 0u) |
+                (j4 + 2 < G && rank_key(v.z, j4 + 2) >= c ? 4u : 0u) | (j4 + 3 < G && rank_key(v.w, j4 + 3) >= c ? 8u : 0u);
+        }
+        unsigned word = nib << (4 * (tid & 7));
+        word |= __shfl_xor(word, 1);
+        word |= __shfl_xor(word, 2);
+        word |= __shfl_xor(word, 4);
+        if ((tid & 7) == 0 && (j4 >> 5) < Gw) keep_bits[row * Gw + (j4 >> 5)] = word;
+      }
+    }
+  };
+
+  // [rmin, rmax]: range of the scores (collected by the scores kernel)
   const float width = rmax - rmin;
-  const float inv = width > 0.0f ? (float)kBins / width : 0.0f;
+  const float inv = width > 0.0f ? (float)BINS / width : 0.0f;
   auto value_bin = [&](float v) -> int {   // bin 0 holds the largest scores
     const int b = (int)((rmax - v) * inv);
-    return b < 0 ? 0 : (b > kBins - 1 ? kBins - 1 : b);
+    return b < 0 ? 0 : (b > BINS - 1 ? BINS - 1 : b);
   };
 
   // pass 2: mass of the row and its histogram over the score range
-  for (int i = tid; i < kBins; i += kSelThreads) {
+  for (int i = tid; i < BINS; i += THREADS) {
     sh.mass[i] = 0;
-    sh.cnt[i] = 0;
+    if constexpr (WITH_CNT) sh.cnt[i] = 0;
   }
   __syncthreads();
-  unsigned long long zl = 0;
-  for_each_score(s, G, [&](float v, int) {
-    const unsigned long long w = weight_of(v, rmax);
-    zl += w;
+  for_each_score<THREADS>(s, G, [&](float v, int) {
     const int b = value_bin(v);
-    atomicAdd(&sh.mass[b], w);
-    atomicAdd(&sh.cnt[b], 1u);
+    atomicAdd(&sh.mass[b], weight_of(v, rmax));
+    if constexpr (WITH_CNT) atomicAdd(&sh.cnt[b], 1u);
   });
-  const unsigned long long Z = block_sum_u64(sh, zl);
-  if (tid == 0) {
-    double t = ceil((double)top_p * (double)Z);
-    unsigned long long T = t < 1.0 ? 1ull : (unsigned long long)t;
-    if (T > Z) T = Z;
-    sh.target = T;
-    sh.mass_above = 0;
-    sh.n_above = 0;
-    sh.done = 0;
-  }
   __syncthreads();
-  locate_bin(sh);
+  locate_bin<true>(sh, top_p);
+
+  // Without counts in the histogram (the row is in LDS, passes are cheap): one pass that counts the scores
+  // ranked above the crossing bin and collects the rank keys of its members, as many as fit the sort.
+  // cls(v): -1 above the bin, 0 inside, +1 below or outside what was the bin before.
+  auto count_and_collect = [&](auto&& cls) {
+    if (tid == 0) sh.ncand = 0;
+    __syncthreads();
+    unsigned na = 0;
+    for_each_score<THREADS>(s, G, [&](float v, int j) {
+      const int c = cls(v);
+      if (c < 0) na++;
+      if (c == 0) {
+        const unsigned pos = atomicAdd(&sh.ncand, 1u);
+        if (pos < (unsigned)CAP) sh.cand[pos] = rank_key(v, j);
+      }
+    });
+    const unsigned long long na_all = block_sum_u64(sh, (unsigned long long)na);   // (its barriers also order the atomics before the read of ncand)
+    if (tid == 0) {
+      sh.n_above += (unsigned)na_all;
+      sh.bin_cnt = sh.ncand;
+    }
+    __syncthreads();
+  };
+  if constexpr (!WITH_CNT) {
+    const int b0 = (int)sh.bin;
+    count_and_collect([&](float v) {
+      const int b = value_bin(v);
+      return b < b0 ? -1 : (b == b0 ? 0 : 1);
+    });
+  }
 
   // The members of the crossing bin form a contiguous stretch of the ranking.  While there are too many to
   // sort, narrow the stretch: take the range [klo, khi] of their ordered score bits and histogram it again,
-  // now linearly in those bits (every round divides the range by kBins, so a few rounds reach a single value).
+  // now linearly in those bits (every round divides the range by BINS, so a few rounds reach a single value).
   bool by_value = true;     // how the current bin is defined: value_bin() == bin, or key range [klo, khi]
   unsigned klo = 0, khi = 0;
   for (int round = 0; round < 6; round++) {
     const unsigned bin = sh.bin;
-    if (sh.bin_cnt <= (unsigned)kCap) break;
+    if (sh.bin_cnt <= (unsigned)CAP) break;
     // range of ordered bits inside the current bin
     if (tid == 0) {
       sh.klo = 0xFFFFFFFFu;
@@ -314,7 +519,7 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
     }
     __syncthreads();
     unsigned lo = 0xFFFFFFFFu, hi = 0u;
-    for_each_score(s, G, [&](float v, int) {
+    for_each_score<THREADS>(s, G, [&, bin, by_value, klo, khi](float v, int) {
       const unsigned o = ordered_bits(v);
       const bool in = by_value ? (value_bin(v) == (int)bin) : (o >= klo && o <= khi);
       if (in) {
@@ -330,27 +535,34 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
     by_value = false;
     if (klo == khi) break;   // one score value left: a run of equal scores, handled by id below
     const unsigned long long R = (unsigned long long)(khi - klo) + 1ull;
-    for (int i = tid; i < kBins; i += kSelThreads) {
+    for (int i = tid; i < BINS; i += THREADS) {
       sh.mass[i] = 0;
-      sh.cnt[i] = 0;
+      if constexpr (WITH_CNT) sh.cnt[i] = 0;
     }
     __syncthreads();
-    for_each_score(s, G, [&](float v, int) {
+    for_each_score<THREADS>(s, G, [&](float v, int) {
       const unsigned o = ordered_bits(v);
       if (o >= klo && o <= khi) {
-        const int b = (int)(((unsigned long long)(khi - o) * kBins) / R);
+        const int b = (int)(((unsigned long long)(khi - o) * BINS) / R);
         atomicAdd(&sh.mass[b], weight_of(v, rmax));
-        atomicAdd(&sh.cnt[b], 1u);
+        if constexpr (WITH_CNT) atomicAdd(&sh.cnt[b], 1u);
       }
     });
     __syncthreads();
-    locate_bin(sh);
-    // ordered bits of the new bin b: khi - o in [ceil(b*R/kBins), ceil((b+1)*R/kBins) - 1]
+    locate_bin<false>(sh, top_p);
+    // ordered bits of the new bin b: khi - o in [ceil(b*R/BINS), ceil((b+1)*R/BINS) - 1]
     const unsigned long long b = sh.bin;
-    const unsigned long long d_lo = (b * R + kBins - 1) / kBins;
-    const unsigned long long d_hi = ((b + 1) * R + kBins - 1) / kBins - 1;
+    const unsigned long long d_lo = (b * R + BINS - 1) / BINS;
+    const unsigned long long d_hi = ((b + 1) * R + BINS - 1) / BINS - 1;
     const unsigned nkhi = khi - (unsigned)d_lo;
     const unsigned nklo = khi - (unsigned)(d_hi > (unsigned long long)(khi - klo) ? (khi - klo) : d_hi);
+    if constexpr (!WITH_CNT) {
+      const unsigned old_hi = khi;
+      count_and_collect([&](float v) {
+        const unsigned o = ordered_bits(v);
+        return (o > nkhi && o <= old_hi) ? -1 : ((o >= nklo && o <= nkhi) ? 0 : 1);
+      });
+    }
     khi = nkhi;
     klo = nklo;
     __syncthreads();
@@ -360,70 +572,99 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
   const unsigned bin_cnt = sh.bin_cnt;
   if (bin_cnt == 0) {   // unreachable (the crossing bin has mass, hence members); kept so that no path leaves the outputs unset
     if (tid == 0) {
+      sh.cut = ~0ull;
       cut[row] = ~0ull;
       count[row] = sh.n_above;
     }
+    write_bits();
     return;
   }
-  if (bin_cnt <= (unsigned)kCap) {
+  if (bin_cnt <= (unsigned)CAP) {
     // sort the members of the crossing bin by rank key (descending) and walk their masses
-    if (tid == 0) sh.ncand = 0;
     int n2 = 1;
     while (n2 < (int)bin_cnt) n2 <<= 1;
-    for (int i = tid; i < n2; i += kSelThreads) sh.cand[i] = 0ull;
-    __syncthreads();
-    for_each_score(s, G, [&](float v, int j) {
-      const unsigned o = ordered_bits(v);
-      const bool in = by_value ? (value_bin(v) == (int)bin) : (o >= klo && o <= khi);
-      if (in) {
-        const unsigned pos = atomicAdd(&sh.ncand, 1u);
-        if (pos < (unsigned)kCap) sh.cand[pos] = rank_key(v, j);
-      }
-    });
-    __syncthreads();
-    for (int k = 2; k <= n2; k <<= 1)
-      for (int jj = k >> 1; jj > 0; jj >>= 1) {
-        for (int i = tid; i < n2; i += kSelThreads) {
-          const int l = i ^ jj;
-          if (l > i) {
-            const unsigned long long a = sh.cand[i], b = sh.cand[l];
-            const bool desc = (i & k) == 0;
-            if (desc ? (a < b) : (a > b)) {
-              sh.cand[i] = b;
-              sh.cand[l] = a;
-            }
-          }
+    if constexpr (WITH_CNT) {
+      if (tid == 0) sh.ncand = 0;
+      for (int i = tid; i < n2; i += THREADS) sh.cand[i] = 0ull;
+      __syncthreads();
+      for_each_score<THREADS>(s, G, [&, bin, by_value, klo, khi](float v, int j) {
+        const unsigned o = ordered_bits(v);
+        const bool in = by_value ? (value_bin(v) == (int)bin) : (o >= klo && o <= khi);
+        if (in) {
+          const unsigned pos = atomicAdd(&sh.ncand, 1u);
+          if (pos < (unsigned)CAP) sh.cand[pos] = rank_key(v, j);
         }
-        __syncthreads();
+      });
+    } else {
+      for (int i = (int)bin_cnt + tid; i < n2; i += THREADS) sh.cand[i] = 0ull;   // the members are there already
+    }
+    __syncthreads();
+    if (bin_cnt <= 64u) {
+      // few members (the usual case): the first wave ranks them by counting, orders their masses by rank and
+      // finds the crossing with a prefix over its lanes
+      if (tid < 64) {
+        const int n = (int)bin_cnt;
+        const unsigned long long key = tid < n ? sh.cand[tid] : 0ull;
+        int rank = 0;
+        for (int j = 0; j < n; j++) rank += sh.cand[j] > key ? 1 : 0;   // keys are distinct
+        if (tid < n) {
+          sh.mass[rank] = weight_of(from_ordered((unsigned)(key >> 32)), rmax);
+          sh.mass[64 + rank] = key;
+        }
+        unsigned long long inc = tid < n ? sh.mass[tid] : 0ull;   // (same wave: LDS accesses complete in order)
+        for (int off = 1; off < 64; off <<= 1) {
+          const unsigned long long up = __shfl_up(inc, off);
+          if (tid >= off) inc += up;
+        }
+        const unsigned long long reached = __ballot(tid < n && sh.mass_above + inc >= sh.target);
+        const int idx = reached ? __ffsll((long long)reached) - 1 : n - 1;   // (the last one if the masses fell short)
+        if (tid == idx) {
+          const unsigned long long c = sh.mass[64 + idx];
+          sh.cut = c;
+          cut[row] = c;
+          count[row] = sh.n_above + (unsigned)idx + 1u;
+        }
       }
-    // first position t where mass_above + (masses of cand[0..t]) reaches the target
-    constexpr int PER = kCap / kSelThreads;
+      write_bits();
+      return;
+    }
+    sort_candidates<THREADS>(sh, n2);
+    // first position where mass_above + (masses of cand[0..position]) reaches the target: every thread owns
+    // CAP / THREADS consecutive candidates, a prefix over the threads names the owner of the crossing
+    constexpr int PER = CAP / THREADS;
+    const unsigned long long target = sh.target, base = sh.mass_above;
+    const int lastc = (int)bin_cnt - 1;
     unsigned long long local = 0;
     for (int i = 0; i < PER; i++) {
       const int idx = tid * PER + i;
-      if (idx < (int)bin_cnt) local += weight_of(from_ordered((unsigned)(sh.cand[idx] >> 32)), rmax);
+      if (idx <= lastc) local += weight_of(from_ordered((unsigned)(sh.cand[idx] >> 32)), rmax);
     }
-    sh.red64[tid] = local;
-    __syncthreads();
-    if (tid == 0) {
-      unsigned long long run = sh.mass_above;
-      int t = 0;
-      while (t < kSelThreads - 1 && run + sh.red64[t] < sh.target) run += sh.red64[t++];
-      int idx = t * PER;
-      const int lastc = (int)bin_cnt - 1;
-      if (idx > lastc) idx = lastc;
-      while (idx < lastc) {
+    unsigned long long em;
+    unsigned en;
+    unsigned long long all;
+    block_exclusive_mass(sh, local, 0u, &em, &en, &all);
+    const unsigned long long lo = base + em;
+    // (the second clause names the last candidate if the masses fell short of the target, the third the first
+    // one if the target was already reached; neither happens with a consistent histogram)
+    const bool mine = (lo < target && (target <= lo + local || tid == lastc / PER)) || (tid == 0 && target <= lo);
+    if (mine && tid * PER <= lastc) {
+      unsigned long long run = lo;
+      int idx = tid * PER;
+      const int stop = min(lastc, tid * PER + PER - 1);
+      while (idx < stop) {
         run += weight_of(from_ordered((unsigned)(sh.cand[idx] >> 32)), rmax);
-        if (run >= sh.target) break;
+        if (run >= target) break;
         idx++;
       }
+      sh.cut = sh.cand[idx];
       cut[row] = sh.cand[idx];
       count[row] = sh.n_above + (unsigned)idx + 1u;
     }
+    write_bits();
     return;
   }
 
-  // A run of more than kCap equal scores contains the crossing: all of them weigh the same, so the number
+  // A run of more than CAP equal scores contains the crossing: all of them weigh the same, so the number
   // to keep follows by division, and they are taken in ascending id.
   const float v_eq = from_ordered(klo);
   const unsigned long long w_eq = weight_of(v_eq, rmax);
@@ -432,7 +673,7 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
   if (t_keep < 1) t_keep = 1;
   if (t_keep > bin_cnt) t_keep = bin_cnt;
   unsigned run = 0;   // members seen in the chunks before this one (the same in every thread)
-  for (int base = 0; base < G && (unsigned long long)run < t_keep; base += kSelThreads * 4) {
+  for (int base = 0; base < G && (unsigned long long)run < t_keep; base += THREADS * 4) {
     const int j4 = base + tid * 4;
     bool in[4] = {false, false, false, false};
     if (j4 < G) {
@@ -443,13 +684,65 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(const float* scores
       in[3] = j4 + 3 < G && ordered_bits(v.w) == klo;
     }
     unsigned total;
-    unsigned pos = run + block_exclusive((unsigned)in[0] + in[1] + in[2] + in[3], sh.cnt, &total);
+    unsigned pos = run + block_exclusive<THREADS>((unsigned)in[0] + in[1] + in[2] + in[3], sh.cnt, &total);
+#pragma unroll
     for (int e = 0; e < 4; e++)
       if (in[e] && (unsigned long long)(++pos) == t_keep) {
+        sh.cut = rank_key(v_eq, j4 + e);
         cut[row] = rank_key(v_eq, j4 + e);
         count[row] = sh.n_above + (unsigned)t_keep;
       }
     run += total;
+  }
+  write_bits();
+}
+
+// One workgroup per query block, rows read from device memory in every pass.
+template <int THREADS, int BINS, int CAP>
+__global__ void __launch_bounds__(THREADS) select_kernel(const float* scores, const unsigned* range, int G, int Gs,
+                                                         float top_p, unsigned long long* cut, unsigned* count) {
+  __shared__ SelShared<THREADS, BINS, CAP, true> sh;
+  const int64_t row = blockIdx.x;
+  select_row<THREADS, BINS, CAP, false>(sh, scores + row * Gs, row, from_ordered(range[2 * row]),
+                                        from_ordered(range[2 * row + 1]), G, top_p, cut, count, nullptr, 0);
+}
+
+// Rows of at most kRowLdsFloats scores: persistent workgroups (one per compute unit: a row takes most of the
+// LDS).  A row is read from device memory once, into registers while the row before it is being processed,
+// then copied to dynamic LDS, and every pass runs on that copy.
+template <int THREADS, int BINS, int CAP>
+__global__ void __launch_bounds__(THREADS) select_lds_kernel(const float* scores, const unsigned* range, int64_t rows,
+                                                             int G, int Gs, float top_p, unsigned long long* cut,
+                                                             unsigned* count, uint32_t* keep_bits, int Gw) {
+  static_assert(THREADS * 4 * 8 == kRowLdsFloats, "eight float4 per thread cover the largest row");
+  __shared__ SelShared<THREADS, BINS, CAP, false> sh;
+  extern __shared__ __attribute__((aligned(16))) float row_lds[];
+  const int tid = threadIdx.x;
+  float4 st[8];
+  unsigned r_hi = 0, r_lo = 0;
+  auto fetch = [&](int64_t row) {
+    const float* s = scores + row * Gs;
+    r_hi = range[2 * row];
+    r_lo = range[2 * row + 1];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      const int j4 = (i * THREADS + tid) * 4;
+      st[i] = j4 < Gs ? *reinterpret_cast<const float4*>(s + j4) : float4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+  };
+  int64_t row = blockIdx.x;
+  if (row < rows) fetch(row);
+  for (; row < rows; row += gridDim.x) {
+    __syncthreads();   // the row before this one has been read for the last time
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      const int j4 = (i * THREADS + tid) * 4;
+      if (j4 < Gs) *reinterpret_cast<float4*>(row_lds + j4) = st[i];
+    }
+    const float rmax = from_ordered(r_hi), rmin = from_ordered(r_lo);
+    __syncthreads();
+    if (row + gridDim.x < rows) fetch(row + gridDim.x);
+    select_row<THREADS, BINS, CAP, true>(sh, row_lds, row, rmax, rmin, G, top_p, cut, count, keep_bits, Gw);
   }
 }
 
@@ -510,7 +803,7 @@ __global__ void __launch_bounds__(kSelThreads) emit_kernel(const float* scores, 
       keep[3] = j4 + 3 < G && rank_key(v.w, j4 + 3) >= c;
     }
     unsigned total;
-    int64_t pos = out0 + run + block_exclusive((unsigned)keep[0] + keep[1] + keep[2] + keep[3], wave_tot, &total);
+    int64_t pos = out0 + run + block_exclusive<kSelThreads>((unsigned)keep[0] + keep[1] + keep[2] + keep[3], wave_tot, &total);
     for (int e = 0; e < 4; e++)
       if (keep[e]) {
         if (pos < capacity) indices[pos] = j4 + e;
@@ -520,12 +813,42 @@ __global__ void __launch_bounds__(kSelThreads) emit_kernel(const float* scores, 
   }
 }
 
+// The same from the bit rows that the LDS-row selection leaves: 256 words (8192 key blocks) per step, ids
+// collected in LDS in ascending order and written out as one contiguous stretch.
+__global__ void __launch_bounds__(kSelThreads) emit_bits_kernel(const uint32_t* keep_bits, int Gw, const int64_t* indptr,
+                                                                int32_t* indices, int64_t capacity) {
+  __shared__ unsigned wave_tot[4];
+  __shared__ int32_t stage[kSelThreads * 32];
+  const int tid = threadIdx.x;
+  const int64_t row = blockIdx.x;
+  const uint32_t* bits = keep_bits + row * Gw;
+  int64_t out = indptr[row];
+  uint32_t nxt = tid < Gw ? bits[tid] : 0u;
+  for (int base = 0; base < Gw; base += kSelThreads) {
+    const int wd = base + tid;
+    uint32_t word = nxt;
+    nxt = wd + kSelThreads < Gw ? bits[wd + kSelThreads] : 0u;
+    unsigned total;
+    unsigned pos = block_exclusive<kSelThreads>((unsigned)__popc(word), wave_tot, &total);
+    while (word) {
+      stage[pos++] = wd * 32 + (__ffs(word) - 1);
+      word &= word - 1;
+    }
+    __syncthreads();
+    for (unsigned i = tid; i < total; i += kSelThreads)
+      if (out + i < capacity) indices[out + i] = stage[i];
+    out += total;
+    __syncthreads();
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 struct Layout {
-  int64_t rows, QB, G, Gs, slices;
-  size_t qp_off, kp_off, scores_off, cut_off, count_off, range_off, total;
+  int64_t rows, QB, G, Gs, Gw, slices;
+  bool row_in_lds;   // rows of scores fit the LDS-row selection kernel
+  size_t qp_off, kp_off, scores_off, cut_off, count_off, range_off, bits_off, total;
 };
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -536,10 +859,13 @@ static int layout_of(const fgattn_params* p, Layout* lo) {
   if (p->d != 64 && p->d != 128) return FGATTN_E_SHAPE;
   if (p->M != 16 && p->M != 32 && p->M != 64 && p->M != 128) return FGATTN_E_SHAPE;
   if (p->L > (1 << 24)) return FGATTN_E_SHAPE;
+  if (p->flags & ~15) return FGATTN_E_FLAGS;
   lo->slices = (int64_t)p->B * p->H;
   lo->QB = ((int64_t)p->L + p->M - 1) / p->M;
   lo->G = ((int64_t)p->L + p->N - 1) / p->N;
-  lo->Gs = (lo->G + 3) & ~(int64_t)3;
+  lo->Gs = (lo->G + 31) & ~(int64_t)31;   // rows start on 128-byte lines
+  lo->Gw = (lo->G + 31) / 32;
+  lo->row_in_lds = lo->Gs <= kRowLdsFloats && !(p->flags & FGATTN_FLAG_MASK_ROWS_IN_HBM);
   lo->rows = lo->slices * lo->QB;
   if (lo->rows > 0x7fffffffLL || lo->slices > 65535) return FGATTN_E_SHAPE;
   size_t off = 0;
@@ -555,19 +881,25 @@ static int layout_of(const fgattn_params* p, Layout* lo) {
   off = align256(off + (size_t)lo->rows * 4);
   lo->range_off = off;
   off = align256(off + (size_t)lo->rows * 8);
+  lo->bits_off = off;
+  if (lo->row_in_lds) off = align256(off + (size_t)lo->rows * lo->Gw * 4);
   lo->total = off;
   return FGATTN_OK;
 }
 
-static int device_ok() {
+// gfx950 or an error; *cus (if given) gets the number of compute units
+static int device_ok(int* cus = nullptr) {
   static int known[64];   // 0 unknown, 1 gfx950, 2 other
+  static int units[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
   if (known[dev] == 0) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return FGATTN_E_DEVICE;
+    units[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
     known[dev] = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 2;
   }
+  if (cus) *cus = units[dev];
   return known[dev] == 1 ? FGATTN_OK : FGATTN_E_DEVICE;
 }
 
@@ -599,7 +931,8 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
     if (strides[i] < 0 || (strides[i] % 8) != 0) return FGATTN_E_STRIDE;
   if (p->q_stride_l < p->d || p->k_stride_l < p->d) return FGATTN_E_STRIDE;
   if (workspace_bytes < lo.total) return FGATTN_E_WORKSPACE;
-  rc = device_ok();
+  int cus = 1;
+  rc = device_ok(&cus);
   if (rc) return rc;
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   char* ws = static_cast<char*>(workspace);
@@ -612,7 +945,7 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
   const uint16_t* qx = static_cast<const uint16_t*>(q);
   const uint16_t* kx = static_cast<const uint16_t*>(k);
 
-  hipLaunchKernelGGL(pool_kernel, dim3((unsigned)lo.QB, (unsigned)lo.slices), dim3(128), 0, stream, qx, p->q_stride_b,
+  hipLaunchKernelGGL(pool_kernel, dim3((unsigned)lo.QB, (unsigned)lo.slices), dim3(64), 0, stream, qx, p->q_stride_b,
                      p->q_stride_h, p->q_stride_l, p->H, p->L, p->d, p->M, (int)lo.QB, qp, range);
   if (!launched()) return FGATTN_E_DEVICE;
   const uint16_t* kmat = kx;
@@ -621,14 +954,14 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
   if (k_in_place) {
     k_slice_stride = p->k_stride_h;
   } else {
-    hipLaunchKernelGGL(pool_kernel, dim3((unsigned)lo.G, (unsigned)lo.slices), dim3(128), 0, stream, kx, p->k_stride_b,
+    hipLaunchKernelGGL(pool_kernel, dim3((unsigned)lo.G, (unsigned)lo.slices), dim3(64), 0, stream, kx, p->k_stride_b,
                        p->k_stride_h, p->k_stride_l, p->H, p->L, p->d, p->N, (int)lo.G, kp, static_cast<unsigned*>(nullptr));
     if (!launched()) return FGATTN_E_DEVICE;
     kmat = kp;
     k_slice_stride = lo.G * p->d;
     k_row_stride = p->d;
   }
-  const dim3 sgrid((unsigned)((lo.G + 4 * kTilesPerWave * 32 - 1) / (4 * kTilesPerWave * 32)), (unsigned)((lo.QB + 31) / 32),
+  const dim3 sgrid((unsigned)((lo.G + kTilesPerGroup * 32 - 1) / (kTilesPerGroup * 32)), (unsigned)((lo.QB + 127) / 128),
                    (unsigned)lo.slices);
   if (p->d == 128)
     hipLaunchKernelGGL(scores_kernel<128>, sgrid, dim3(256), 0, stream, qp, kmat, k_slice_stride, k_row_stride, (int)lo.QB,
@@ -637,8 +970,24 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
     hipLaunchKernelGGL(scores_kernel<64>, sgrid, dim3(256), 0, stream, qp, kmat, k_slice_stride, k_row_stride, (int)lo.QB,
                        (int)lo.G, (int)lo.Gs, p->scale, scores, range);
   if (!launched()) return FGATTN_E_DEVICE;
-  hipLaunchKernelGGL(select_kernel, dim3((unsigned)lo.rows), dim3(kSelThreads), 0, stream, scores, range, (int)lo.G,
-                     (int)lo.Gs, top_p, cut, count);
+  if (lo.row_in_lds) {
+    auto kern = select_lds_kernel<kRowThreads, kRowBins, kRowCap>;
+    static bool lds_set[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
+    if (!lds_set[dev]) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              kRowLdsFloats * 4) != hipSuccess)
+        return FGATTN_E_DEVICE;
+      lds_set[dev] = true;
+    }
+    const unsigned wgs = (unsigned)(lo.rows < cus ? lo.rows : cus);
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(kRowThreads), (size_t)lo.Gs * 4, stream, scores, range, lo.rows, (int)lo.G,
+                       (int)lo.Gs, top_p, cut, count, reinterpret_cast<uint32_t*>(ws + lo.bits_off), (int)lo.Gw);
+  } else {
+    hipLaunchKernelGGL((select_kernel<kSelThreads, kBins, kCap>), dim3((unsigned)lo.rows), dim3(kSelThreads), 0, stream,
+                       scores, range, (int)lo.G, (int)lo.Gs, top_p, cut, count);
+  }
   if (!launched()) return FGATTN_E_DEVICE;
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, count, lo.rows, mask_indptr);
   return launched() ? FGATTN_OK : FGATTN_E_DEVICE;
@@ -659,8 +1008,13 @@ int fgattn_mask_emit(const fgattn_params* p, const int64_t* mask_indptr, int32_t
   const char* ws = static_cast<const char*>(workspace);
   const float* scores = reinterpret_cast<const float*>(ws + lo.scores_off);
   const unsigned long long* cut = reinterpret_cast<const unsigned long long*>(ws + lo.cut_off);
-  hipLaunchKernelGGL(emit_kernel, dim3((unsigned)lo.rows), dim3(kSelThreads), 0, static_cast<hipStream_t>(stream_v), scores,
-                     (int)lo.G, (int)lo.Gs, cut, mask_indptr, mask_indices, indices_capacity);
+  if (lo.row_in_lds)
+    hipLaunchKernelGGL(emit_bits_kernel, dim3((unsigned)lo.rows), dim3(kSelThreads), 0, static_cast<hipStream_t>(stream_v),
+                       reinterpret_cast<const uint32_t*>(ws + lo.bits_off), (int)lo.Gw, mask_indptr, mask_indices,
+                       indices_capacity);
+  else
+    hipLaunchKernelGGL(emit_kernel, dim3((unsigned)lo.rows), dim3(kSelThreads), 0, static_cast<hipStream_t>(stream_v), scores,
+                       (int)lo.G, (int)lo.Gs, cut, mask_indptr, mask_indices, indices_capacity);
   return launched() ? FGATTN_OK : FGATTN_E_DEVICE;
 }
 

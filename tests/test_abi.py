@@ -43,7 +43,7 @@ def test_workspace_bytes_and_shape_validation(lib):
     p = F.FgattnParams(1, 12, 32760, 128, 64, 1, *([0] * 12), 0.1, 0)
     n = lib.fgattn_workspace_bytes(ctypes.byref(p))
     assert n >= 256 + 4 * 12 * 512 and n % 256 == 0
-    for field, bad in (("d", 96), ("M", 24), ("N", 0), ("L", 0), ("H", 0), ("flags", 8)):
+    for field, bad in (("d", 96), ("M", 24), ("N", 0), ("L", 0), ("H", 0), ("flags", 16)):
         q = F.FgattnParams(1, 12, 32760, 128, 64, 1, *([0] * 12), 0.1, 0)
         setattr(q, field, bad)
         assert lib.fgattn_workspace_bytes(ctypes.byref(q)) == 0, field

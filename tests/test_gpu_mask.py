@@ -22,10 +22,10 @@ pytestmark = pytest.mark.gpu
 EPS = 1e-5
 
 
-def gpu_mask(w, q_bits, k_bits, top_p, scale=None, want_pooled=False):
+def gpu_mask(w, q_bits, k_bits, top_p, scale=None, want_pooled=False, flags=0):
     """Runs select + emit; returns (indptr, indices) as numpy (and the Q block means if asked)."""
     q, k = to_dev_bf16(q_bits), to_dev_bf16(k_bits)
-    p = F.make_params(q, k, k, q, w.M, w.N, w.scale if scale is None else scale)
+    p = F.make_params(q, k, k, q, w.M, w.N, w.scale if scale is None else scale, flags)
     nbytes = F.fgattn_mask_workspace_bytes(p)
     assert nbytes > 0
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -74,11 +74,12 @@ def check_rows(oracle, w, q_bits, k_bits, top_p, indptr, indices, rows, scale=No
                                           (128, 32, 128, 1024, (4, 16, 16)), (32, 1, 128, 1000, (10, 10, 10)),
                                           (64, 3, 64, 1000, (10, 10, 10)), (16, 1, 64, 3000, (3, 25, 40))])
 @pytest.mark.parametrize("top_p", [0.5, 0.9])
-def test_mask_matches_oracle_small(oracle_mod, M, N, d, L, grid, top_p):
+@pytest.mark.parametrize("flags", [0, F.FLAG_MASK_ROWS_IN_HBM], ids=["lds-rows", "hbm-rows"])
+def test_mask_matches_oracle_small(oracle_mod, M, N, d, L, grid, top_p, flags):
     w = W.Workload("mask-M%d-N%d-d%d-L%d" % (M, N, d, L), H=2, L=L, d=d, M=M, N=N, grid=grid, seed=4000 + M + N)
     q, k = W.make_qk_local(w, gain=1.5 if d == 64 else 1.2)
     say("mask %s p=%.2f" % (w.name, top_p))
-    indptr, indices, pooled = gpu_mask(w, q, k, top_p, want_pooled=True)
+    indptr, indices, pooled = gpu_mask(w, q, k, top_p, want_pooled=True, flags=flags)
     assert np.array_equal(pooled, oracle_mod.pool(q, M)), "query block means differ from the oracle's bits"
     rows = list(range(w.items))
     bad = check_rows(oracle_mod, w, q, k, top_p, indptr, indices, rows, what=w.name)
@@ -96,15 +97,18 @@ def test_mask_unstructured_inputs(oracle_mod):
     check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, list(range(w.items)), what=w.name)
 
 
-@pytest.mark.parametrize("L,N,top_p,kept", [(1024, 8, 0.75, 96), (8192, 1, 0.75, 6144), (8192, 1, 0.5, 4096)])
-def test_uniform_scores_closed_form(L, N, top_p, kept):
+@pytest.mark.parametrize("L,N,top_p,kept,flags", [(1024, 8, 0.75, 96, 0), (8192, 1, 0.75, 6144, 0), (8192, 1, 0.5, 4096, 0),
+                                                  (1024, 8, 0.75, 96, 8), (8192, 1, 0.5, 4096, 8),
+                                                  (40000, 1, 0.625, 25000, 0)])
+def test_uniform_scores_closed_form(L, N, top_p, kept, flags):
     # Q = 0: all key blocks weigh the same, the mask is the ceil(p*G) lowest ids.  G = 128 goes through the
-    # sorted-bin path, G = 8192 through the run-of-equal-scores path (more members than fit the sort).
-    w = W.Workload("mask-uniform", H=1, L=L, d=64, M=64, N=N, seed=4200)
+    # sorted-bin path, G = 8192 and 40000 through the run-of-equal-scores path (more members than fit the sort);
+    # 40000 key blocks are more than a row kept in LDS holds, so that case selects from device memory by itself.
+    w = W.Workload("mask-uniform", H=1, L=L, d=64, M=64 if L < 40000 else 128, N=N, seed=4200)
     _, k, _ = W.make_qkv(w)
     q = np.zeros_like(k)
     say("mask uniform L=%d N=%d p=%.2f" % (L, N, top_p))
-    indptr, indices = gpu_mask(w, q, k, top_p)
+    indptr, indices = gpu_mask(w, q, k, top_p, flags=flags)
     assert np.array_equal(np.diff(indptr), np.full(w.items, kept))
     for r in range(w.items):
         assert np.array_equal(indices[indptr[r]:indptr[r + 1]], np.arange(kept))
@@ -124,6 +128,18 @@ def test_dominant_key_block_and_p_one(oracle_mod):
     indptr, indices = gpu_mask(w, q, k, 1.0, scale=0.05)
     assert np.all(np.diff(indptr) <= w.G) and np.all(np.diff(indptr) >= 1)
     check_rows(oracle_mod, w, q, k, 1.0, indptr, indices, list(range(w.items)), scale=0.05, what="p=1")
+
+
+def test_mask_rows_longer_than_lds(oracle_mod):
+    # 33000 key blocks: above the 32768 that the LDS-row selection holds; sampled query blocks against the oracle
+    w = W.Workload("mask-long-rows", H=1, L=33000, d=64, M=128, N=1, grid=(10, 55, 60), seed=4500)
+    q, k = W.make_qk_local(w, gain=1.5)
+    say("mask %s" % w.name)
+    indptr, indices = gpu_mask(w, q, k, 0.9)
+    rows = list(range(0, w.items, 13)) + [w.items - 1]
+    bad = check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, what=w.name)
+    assert bad <= 2
+    say("    density %.3f" % (indices.size / float(w.items * w.G)))
 
 
 def test_mask_feeds_forward(oracle_mod):
