@@ -112,6 +112,22 @@ def test_device_grouping_then_forward(oracle_mod):
         check_against_oracle(oracle_mod, prob, got, what=w.name + " " + mode)
 
 
+def test_device_grouping_with_batch(oracle_mod):
+    # B = 2: slices are (batch, head) pairs; ragged last tile and last group (1000 = 31 * 32 + 8; 32 tiles = 8 groups)
+    import dataclasses
+    w = dataclasses.replace(W.Workload("group-batch", H=2, L=1000, d=64, M=32, N=1, grid=(10, 10, 10), window=(1, 2, 2),
+                                       kind=W.MASK_WINDOW_FILL, density=0.3, seed=6400), B=2)
+    prob = Problem(w)
+    for mode in ("xor", "consecutive"):
+        got = gpu_grouping(prob, mode)
+        ref = GR.grouped_mask(prob.indptr, prob.indices, w.B * w.H, w.QB, w.G, 4, mode)
+        for a, b, name in zip(got, ref, ("group_tiles", "union_indptr", "union_indices", "union_members")):
+            assert np.array_equal(a, b), name + " " + mode
+        say("device grouping B=2 %s: union entries %d" % (mode, got[2].size))
+        out = run_grouped(prob, *got)
+        check_against_oracle(oracle_mod, prob, out, what=w.name + " " + mode)
+
+
 def test_grouping_argument_checks():
     prob = Problem(W.TINY)
     p = prob.params()

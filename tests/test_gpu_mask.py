@@ -142,6 +142,31 @@ def test_mask_rows_longer_than_lds(oracle_mod):
     say("    density %.3f" % (indices.size / float(w.items * w.G)))
 
 
+@pytest.mark.parametrize("N", [1, 4])
+def test_mask_batch_and_strided_layout(oracle_mod, N):
+    # B = 2 with [B, L, H, d] storage (heads interleaved) through the stride arguments; last query block is short
+    import dataclasses
+    w = dataclasses.replace(W.Workload("mask-batch-N%d" % N, H=3, L=520, d=128, M=64, N=N, grid=(5, 8, 13), seed=4600 + N), B=2)
+    q, k = W.make_qk_local(w, gain=1.2)
+    say("mask %s, strided" % w.name)
+    tr = lambda t: t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)      # same values, [B,L,H,d] storage
+    dq, dk = tr(to_dev_bf16(q)), tr(to_dev_bf16(k))
+    assert dq.stride(1) == w.d and dq.stride(2) == w.H * w.d
+    p = F.make_params(dq, dk, dk, dq, w.M, w.N, w.scale)
+    ws = torch.empty(F.fgattn_mask_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    rows = w.B * w.H * w.QB
+    indptr = torch.full((rows + 1,), -1, dtype=torch.int64, device="cuda")
+    F.fgattn_mask_select(dq, dk, p, 0.8, indptr, ws)
+    nnz = int(indptr[-1].item())
+    indices = torch.full((nnz,), -7, dtype=torch.int32, device="cuda")
+    F.fgattn_mask_emit(p, indptr, indices, ws)
+    torch.cuda.synchronize()
+    pooled = ws[:rows * w.d * 2].view(torch.int16).cpu().numpy().view(np.uint16).reshape(w.B * w.H, w.QB, w.d)
+    assert np.array_equal(pooled, oracle_mod.pool(q, w.M)), "query block means differ from the oracle's bits"
+    bad = check_rows(oracle_mod, w, q, k, 0.8, indptr.cpu().numpy(), indices.cpu().numpy(), list(range(rows)), what=w.name)
+    assert bad <= 2
+
+
 def test_mask_feeds_forward(oracle_mod):
     # the loop closed on the device: Q, K -> mask -> sparse attention, checked against the oracle run on that mask
     w = W.Workload("mask-then-attend", H=2, L=1024, d=128, M=64, N=8, grid=(4, 16, 16), seed=4400)
