@@ -217,3 +217,24 @@ def test_mask_full_size_wan(oracle_mod):
                   set(rng.choice(w.items, size=43, replace=False).tolist()))
     bad = check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, what=w.name)
     assert bad <= 5
+
+
+def test_mask_full_size_hunyuan(oracle_mod):
+    # config-4 shape: 22296 query blocks x 118800 key blocks (10.6 GB of scores); rows this long are selected from
+    # device memory.  Sampled rows against the oracle, all rows by the validator.
+    w = W.HUNYUAN
+    q, k = W.make_qk_local(w, gain=2.5)
+    say("mask hunyuan p=0.9")
+    indptr, indices = gpu_mask(w, q, k, 0.9)
+    nnz = np.diff(indptr)
+    say("    density %.3f, per block min %d max %d" % (indices.size / float(w.items * w.G), nnz.min(), nnz.max()))
+    d_indptr, d_indices = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    dq = to_dev_bf16(q)
+    p = F.make_params(dq, dq, dq, dq, w.M, w.N, w.scale)
+    ws = torch.empty(F.fgattn_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    assert F.fgattn_validate_mask(d_indptr, d_indices, p, ws) == 0
+    rng = np.random.default_rng(1)
+    rows = sorted({0, w.QB - 1, w.items - 1, int(np.argmax(nnz)), int(np.argmin(nnz))} |
+                  set(rng.choice(w.items, size=11, replace=False).tolist()))
+    bad = check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, what=w.name)
+    assert bad <= 2
