@@ -13,6 +13,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "fgattn.h"
 
 namespace fgg {
@@ -138,6 +140,110 @@ __global__ void __launch_bounds__(kThreads) greedy_kernel(const uint32_t* dist, 
       }
       __syncthreads();
     }
+    if (R == 1) __syncthreads();   // no pick, hence no barrier since seed_s was read
+  }
+}
+
+// Minimum of a 32-bit value over the 64 lanes of a wave, returned in every lane: shifts within rows of 16
+// lanes, then the last lane of a row broadcast into the next row(s); lanes without a source keep the identity.
+__device__ __forceinline__ unsigned wave_min_u32(unsigned x) {
+  constexpr unsigned ID = 0xFFFFFFFFu;
+  auto shifted = [&](unsigned v, auto ctrl, auto row_mask, auto bank_mask) {
+    return (unsigned)__builtin_amdgcn_update_dpp((int)ID, (int)v, decltype(ctrl)::value, decltype(row_mask)::value,
+                                                 decltype(bank_mask)::value, false);
+  };
+  using std::integral_constant;
+  unsigned y = min(x, shifted(x, integral_constant<int, 0x111>(), integral_constant<int, 0xf>(), integral_constant<int, 0xf>()));   // row_shr:1
+  y = min(y, shifted(x, integral_constant<int, 0x112>(), integral_constant<int, 0xf>(), integral_constant<int, 0xf>()));            // row_shr:2
+  y = min(y, shifted(x, integral_constant<int, 0x113>(), integral_constant<int, 0xf>(), integral_constant<int, 0xf>()));            // row_shr:3
+  y = min(y, shifted(y, integral_constant<int, 0x114>(), integral_constant<int, 0xf>(), integral_constant<int, 0xe>()));            // row_shr:4
+  y = min(y, shifted(y, integral_constant<int, 0x118>(), integral_constant<int, 0xf>(), integral_constant<int, 0xc>()));            // row_shr:8
+  y = min(y, shifted(y, integral_constant<int, 0x142>(), integral_constant<int, 0xa>(), integral_constant<int, 0xf>()));            // row_bcast:15
+  y = min(y, shifted(y, integral_constant<int, 0x143>(), integral_constant<int, 0xc>(), integral_constant<int, 0xf>()));            // row_bcast:31
+  return (unsigned)__builtin_amdgcn_readlane((int)y, 63);
+}
+
+// The same heuristic for slices of at most KPT * kThreads tiles whose (distance, index) pairs fit 32 bits
+// (`jbits` for the index): the representative's row of distances is read once per group into registers, KPT
+// keys per thread, and every pick is a register minimum, a wave minimum and one barrier.
+template <int KPT>
+__global__ void __launch_bounds__(kThreads) greedy_small_kernel(const uint32_t* dist, int QB, int R, int NG, int jbits,
+                                                                int32_t* group_tiles) {
+  extern __shared__ unsigned char used[];
+  __shared__ unsigned best[2][kThreads / 64];
+  __shared__ int seed_s, spec_s;
+  const int tid = threadIdx.x, wv = tid >> 6;
+  const int slice = blockIdx.x;
+  const uint32_t* D = dist + (int64_t)slice * QB * QB;
+  int32_t* out = group_tiles + (int64_t)slice * NG * R;
+  const unsigned jmask = (1u << jbits) - 1u;
+  for (int i = tid; i < QB; i += kThreads) used[i] = 0;
+  __syncthreads();
+  int next = 0;        // every tile below `next` is used (the same value in all threads)
+  unsigned round = 0;  // picks so far: selects the half of best[] in use
+  // distances of row `ahead_row`, read one group early: the first unused tile after the representative becomes
+  // the next representative unless this group picks it
+  unsigned ahead[KPT] = {};
+  int ahead_row = -1;
+  for (int g = 0; g < NG; g++) {
+    if (tid == 0) {
+      int s = next;
+      while (s < QB && used[s]) s++;
+      seed_s = s;
+      if (s < QB) used[s] = 1;
+      int c = s + 1;
+      while (c < QB && used[c]) c++;
+      spec_s = c;
+    }
+    __syncthreads();
+    const int seed = seed_s, spec = spec_s;
+    next = seed + 1;
+    if (tid == 0) out[g * R] = seed < QB ? seed : -1;
+    unsigned key[KPT];   // (distance, index) of the unused tiles this thread owns, all ones otherwise
+    const uint32_t* drow = D + (int64_t)(seed < QB ? seed : 0) * QB;
+    // (all loads unconditional, with clamped indices: they are issued back to back, and the rows read ahead stay
+    // in flight while this group picks)
+    unsigned now[KPT];
+#pragma unroll
+    for (int i = 0; i < KPT; i++) now[i] = drow[min(i * kThreads + tid, QB - 1)];
+    const bool have = seed == ahead_row;
+#pragma unroll
+    for (int i = 0; i < KPT; i++) {
+      const int j = i * kThreads + tid;
+      const bool cand = seed < QB && j < QB && !used[j];
+      const unsigned dv = have ? ahead[i] : now[i];
+      key[i] = cand ? ((dv << jbits) | (unsigned)j) : 0xFFFFFFFFu;
+    }
+    ahead_row = spec < QB ? spec : -1;
+    {
+      const uint32_t* srow = D + (int64_t)(spec < QB ? spec : 0) * QB;
+#pragma unroll
+      for (int i = 0; i < KPT; i++) ahead[i] = srow[min(i * kThreads + tid, QB - 1)];
+    }
+    for (int r = 1; r < R; r++, round++) {
+      unsigned mine = key[0];
+#pragma unroll
+      for (int i = 1; i < KPT; i++) mine = min(mine, key[i]);
+      const unsigned w = wave_min_u32(mine);
+      if ((tid & 63) == 0) best[round & 1][wv] = w;
+      __syncthreads();
+      unsigned win = best[round & 1][0];
+#pragma unroll
+      for (int k = 1; k < kThreads / 64; k++) win = min(win, best[round & 1][k]);
+      if (win != 0xFFFFFFFFu) {
+        const int j = (int)(win & jmask);
+#pragma unroll
+        for (int i = 0; i < KPT; i++)
+          if (j == i * kThreads + tid) key[i] = 0xFFFFFFFFu;
+        if (tid == 0) {
+          used[j] = 1;
+          out[g * R + r] = j;
+        }
+      } else if (tid == 0) {
+        out[g * R + r] = -1;
+      }
+    }
+    __syncthreads();   // seed_s is rewritten for the next group (also orders groups without picks, R = 1)
   }
 }
 
@@ -335,8 +441,22 @@ int fgattn_group_select(const int64_t* mask_indptr, const int32_t* mask_indices,
     hipLaunchKernelGGL(distance_kernel, dim3((unsigned)((QB + 63) / 64), (unsigned)((QB + 63) / 64), (unsigned)lo.slices),
                        dim3(kThreads), 0, stream, bits, QB, Gw, dist);
     if (!launched()) return FGATTN_E_DEVICE;
-    hipLaunchKernelGGL(greedy_kernel, dim3((unsigned)lo.slices), dim3(kThreads), (size_t)QB, stream, dist, QB, R, NG,
-                       group_tiles);
+    // a distance is at most twice the number of key blocks; with the tile index below it in 32 bits where it fits
+    int jbits = 1;
+    while ((1 << jbits) < QB) jbits++;
+    const bool small = QB <= 16 * kThreads && (2 * lo.G + 1) < ((int64_t)1 << (32 - jbits));
+    if (small && QB <= 4 * kThreads)
+      hipLaunchKernelGGL(greedy_small_kernel<4>, dim3((unsigned)lo.slices), dim3(kThreads), (size_t)QB, stream, dist, QB, R,
+                         NG, jbits, group_tiles);
+    else if (small && QB <= 8 * kThreads)
+      hipLaunchKernelGGL(greedy_small_kernel<8>, dim3((unsigned)lo.slices), dim3(kThreads), (size_t)QB, stream, dist, QB, R,
+                         NG, jbits, group_tiles);
+    else if (small)
+      hipLaunchKernelGGL(greedy_small_kernel<16>, dim3((unsigned)lo.slices), dim3(kThreads), (size_t)QB, stream, dist, QB, R,
+                         NG, jbits, group_tiles);
+    else
+      hipLaunchKernelGGL(greedy_kernel, dim3((unsigned)lo.slices), dim3(kThreads), (size_t)QB, stream, dist, QB, R, NG,
+                         group_tiles);
   }
   if (!launched()) return FGATTN_E_DEVICE;
   hipLaunchKernelGGL(union_kernel, dim3((unsigned)lo.groups), dim3(kThreads), 0, stream, bits, group_tiles, QB, Gw, R, NG,

@@ -100,6 +100,17 @@ def test_device_grouping_equals_the_oracles(mode, M, N, L, kind):
         assert np.array_equal(a, b), name
 
 
+def test_device_grouping_many_tiles():
+    # 4688 tiles per slice: more than the register-resident variant of the greedy pre-pass takes
+    w = W.Workload("grouping-many-tiles", H=1, L=75000, d=64, M=16, N=64, kind=W.MASK_RANDOM, density=0.3, seed=6500)
+    prob = Problem(w)
+    say("device grouping %s: %d tiles, %d key blocks" % (w.name, w.QB, w.G))
+    got = gpu_grouping(prob, "xor")
+    ref = GR.grouped_mask(prob.indptr, prob.indices, w.H, w.QB, w.G, 8, "xor")
+    for a, b, name in zip(got, ref, ("group_tiles", "union_indptr", "union_indices", "union_members")):
+        assert np.array_equal(a, b), name
+
+
 def test_device_grouping_then_forward(oracle_mod):
     # everything on the device: mask -> grouping -> grouped attention, against the oracle on the ungrouped mask
     w = W.Workload("group-then-attend", H=2, L=2048, d=128, M=32, N=1, grid=(8, 16, 16), window=(1, 3, 3),
