@@ -97,7 +97,7 @@ int fgattn_dense_forward(const void* q, const void* k, const void* v, const fgat
 /* Measurement aid, not part of the method: runs one half of fgattn_forward's kernel on the same launch shape,
  * FGATTN_PART_GATHER = index translation and K/V row gathers only (the data movement of Sec. 4.1),
  * FGATTN_PART_COMPUTE = everything except the row gathers (MFMA, softmax, LDS reads on whatever the tiles hold).
- * Same arguments and error behaviour as fgattn_forward; only M = 64, d = 128, N = 1 is built (else
+ * Same arguments and error behaviour as fgattn_forward; only M = 64 or 128 with d = 128, N = 1 is built (else
  * FGATTN_E_SHAPE; an unknown `part` gives FGATTN_E_FLAGS).  `out` and `lse` are overwritten with meaningless
  * values. */
 #define FGATTN_PART_GATHER 1

@@ -290,7 +290,7 @@ int fgattn_forward_part(const void* q, const void* k, const void* v, const int64
                         size_t workspace_bytes, int part, void* stream) {
   if (!mask_indptr || !mask_indices) return FGATTN_E_NULL;
   if (part != FGATTN_PART_GATHER && part != FGATTN_PART_COMPUTE) return FGATTN_E_FLAGS;
-  if (p && (p->M != 64 || p->d != 128 || p->N != 1)) return FGATTN_E_SHAPE;
+  if (p && ((p->M != 64 && p->M != 128) || p->d != 128 || p->N != 1)) return FGATTN_E_SHAPE;
   return fg::run_forward(q, k, v, mask_indptr, mask_indices, p, out, lse, workspace, workspace_bytes, stream, part);
 }
 

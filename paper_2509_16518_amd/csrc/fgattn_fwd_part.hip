@@ -7,7 +7,13 @@
 namespace fg {
 
 int launch_part(const FwdArgs& a, int part, int cus, hipStream_t stream) {
-  static int occ[2][64];
+  static int occ[4][64];
+  if (a.M == 128) {
+    constexpr int lds = FwdCfg<128, 128>::LDS_BYTES;
+    if (part == PART_GATHER)
+      return launch_variant(fgattn_fwd_kernel<128, 128, NMODE_N1, 2, PART_GATHER>, lds, a, cus, stream, nullptr, occ[2]);
+    return launch_variant(fgattn_fwd_kernel<128, 128, NMODE_N1, 2, PART_COMPUTE>, lds, a, cus, stream, nullptr, occ[3]);
+  }
   constexpr int lds = FwdCfg<64, 128>::LDS_BYTES;
   if (part == PART_GATHER)
     return launch_variant(fgattn_fwd_kernel<64, 128, NMODE_N1, 2, PART_GATHER>, lds, a, cus, stream, nullptr, occ[0]);

@@ -62,9 +62,10 @@ def test_validate_mask_flags_bad_masks():
     assert F.fgattn_validate_mask(dec, prob.d_indices, p, ws) == F.E_MASK
 
 
-def test_forward_part_is_a_measurement_aid_only():
-    # built for M = 64, d = 128, N = 1 only; runs, leaves the real entry point's results untouched afterwards
-    w = W.Workload("part", H=2, L=2048, d=128, M=64, N=1, kind=W.MASK_RANDOM, density=0.3, seed=5100)
+@pytest.mark.parametrize("M", [64, 128])
+def test_forward_part_is_a_measurement_aid_only(M):
+    # built for M = 64 / 128, d = 128, N = 1 only; runs, leaves the real entry point's results untouched afterwards
+    w = W.Workload("part", H=2, L=2048, d=128, M=M, N=1, kind=W.MASK_RANDOM, density=0.3, seed=5100)
     prob = Problem(w)
     p = prob.params(flags=F.FLAG_REUSE_PLAN)
     ws = prob.workspace(p)
