@@ -284,8 +284,7 @@ struct SelShared {
   unsigned long long wave_m[THREADS / 64];
   unsigned wave_n[THREADS / 64];
   unsigned long long mass_above, target, cut;
-  unsigned n_above, bin, bin_cnt, ncand, klo, khi, run;
-  int done;
+  unsigned n_above, bin, bin_cnt, ncand, klo, khi;
 };
 
 template <int THREADS, int BINS, int CAP, bool WITH_CNT>

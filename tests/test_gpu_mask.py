@@ -99,12 +99,14 @@ def test_mask_unstructured_inputs(oracle_mod):
 
 @pytest.mark.parametrize("L,N,top_p,kept,flags", [(1024, 8, 0.75, 96, 0), (8192, 1, 0.75, 6144, 0), (8192, 1, 0.5, 4096, 0),
                                                   (1024, 8, 0.75, 96, 8), (8192, 1, 0.5, 4096, 8),
-                                                  (40000, 1, 0.625, 25000, 0)])
+                                                  (40000, 1, 0.625, 25000, 0), (32768, 1, 0.5, 16384, 0),
+                                                  (32767, 1, 0.5, 16384, 0), (32769, 1, 0.5, 16385, 0)])
 def test_uniform_scores_closed_form(L, N, top_p, kept, flags):
     # Q = 0: all key blocks weigh the same, the mask is the ceil(p*G) lowest ids.  G = 128 goes through the
     # sorted-bin path, G = 8192 and 40000 through the run-of-equal-scores path (more members than fit the sort);
     # 40000 key blocks are more than a row kept in LDS holds, so that case selects from device memory by itself.
-    w = W.Workload("mask-uniform", H=1, L=L, d=64, M=64 if L < 40000 else 128, N=N, seed=4200)
+    # (32768 key blocks fill the LDS row exactly; one more takes the other path)
+    w = W.Workload("mask-uniform", H=1, L=L, d=64, M=64 if L < 30000 else 128, N=N, seed=4200)
     _, k, _ = W.make_qkv(w)
     q = np.zeros_like(k)
     say("mask uniform L=%d N=%d p=%.2f" % (L, N, top_p))
