@@ -6,7 +6,7 @@ or tiles with similar key sets (greedy merge-XOR), and reports planning and kern
 on the same masks: the ungrouped kernel (this library runs small tiles natively), and the grouped kernel with both
 groupings, with the grouping pre-pass ("planning") timed separately.  Prints one JSON object per line.
 
-    python -m paper_2509_16518_amd.grouping_bench [--heads 12] [--tokens 32760] [--steps 5]
+    python -m paper_2509_16518_amd.grouping_bench [--heads 12] [--tokens 32760] [--steps 5] [--density 0.3]
 """
 import argparse
 import json
@@ -23,6 +23,7 @@ def main():
     ap.add_argument("--head-dim", type=int, default=128)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--blocks", type=int, nargs="*", default=[64, 32, 16])
+    ap.add_argument("--density", type=float, default=0.30, help="1 - sparsity of the masks (the paper uses 0.3 and 0.5)")
     args = ap.parse_args()
 
     import torch
@@ -58,7 +59,7 @@ def main():
     for blk in args.blocks:
         for mname, kind, window in masks:
             w = W.Workload(base.name, H=base.H, L=base.L, d=base.d, M=blk, N=blk, grid=tuple(args.grid), window=window,
-                           kind=kind, density=0.30, seed=8000 + blk)
+                           kind=kind, density=args.density, seed=8000 + blk)
             indptr, indices = W.make_mask(w)
             useful = W.useful_flop(w, indptr, indices)
             d_indptr, d_indices = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
