@@ -3,11 +3,11 @@
 
 For each (sparsity, skew) a mask is drawn with the paper's generator -- per query block a list length uniform in
 [(1 - skew) * Lmax, Lmax] and that many random key blocks, Lmax chosen so that the mean density is the target --
-at block size 128 x 32, and the sparse kernel is timed with the longest-first work queue and with static
+at block size 128 x 32 (or --block-m / --block-n), and the sparse kernel is timed with the longest-first work queue and with static
 assignment of query blocks to workgroups (the paper's "no scheduler"), next to the same build's dense kernel.
 Prints one JSON object per line.
 
-    python -m paper_2509_16518_amd.ablation [--heads 12] [--tokens 32760] [--steps 10]
+    python -m paper_2509_16518_amd.ablation [--heads 12] [--tokens 32760] [--steps 10] [--block-m 128 --block-n 32]
 """
 import argparse
 import json
@@ -22,6 +22,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=32760)
     ap.add_argument("--head-dim", type=int, default=128)
     ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--block-m", type=int, default=128, help="query rows per block")
+    ap.add_argument("--block-n", type=int, default=32, help="keys per block")
     ap.add_argument("--sparsity", type=float, nargs="*", default=[0.5, 0.7, 0.9])
     ap.add_argument("--skew", type=float, nargs="*", default=[0.0, 0.25, 0.5, 0.75, 1.0])
     args = ap.parse_args()
@@ -49,7 +51,7 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps
 
-    base = W.Workload("skew-ablation", H=args.heads, L=args.tokens, d=args.head_dim, M=128, N=32,
+    base = W.Workload("skew-ablation", H=args.heads, L=args.tokens, d=args.head_dim, M=args.block_m, N=args.block_n,
                       kind=W.MASK_SKEW_LEN, seed=7000)
     q, k, v = W.make_qkv(base)
     dq, dk, dv = dev(q), dev(k), dev(v)

@@ -174,8 +174,10 @@ __device__ __forceinline__ void softmax_max(f32x16& S, const float* bias_keys, i
 // NMODE selects how a compacted key position maps to a key row:
 //   NMODE_DENSE   position == key (0% sparsity, no index list);
 //   NMODE_N1      one key per group: key = indices[position];
-//   NMODE_GROUPS  N >= 1 keys per group: key = indices[position / N] * N + position % N.
-enum { NMODE_DENSE = 0, NMODE_N1 = 1, NMODE_GROUPS = 2 };
+//   NMODE_GROUPS  N >= 1 keys per group: key = indices[position / N] * N + position % N, L a multiple of N;
+//   NMODE_GROUPS_SHORT  the same with a short last group (L not a multiple of N): any tile may then hold
+//                 positions past the end of the sequence, which are masked out.
+enum { NMODE_DENSE = 0, NMODE_N1 = 1, NMODE_GROUPS = 2, NMODE_GROUPS_SHORT = 3 };
 
 // PART selects what is executed: PART_ALL is the forward pass; PART_GATHER keeps only the index translation and
 // the row gathers, PART_COMPUTE everything but the row gathers (both leave meaningless results and exist so that
@@ -190,7 +192,8 @@ template <int MT, int D, int NMODE, int OCC, int PART = PART_ALL, bool GROUPED =
 __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
   using C = FwdCfg<MT, D>;
   constexpr bool DENSE = NMODE == NMODE_DENSE;
-  static_assert(!GROUPED || (MT == 128 && NMODE != NMODE_DENSE), "groups are 128 query rows with a sparse list");
+  static_assert(!GROUPED || (MT == 128 && (NMODE == NMODE_N1 || NMODE == NMODE_GROUPS_SHORT)),
+                "groups are 128 query rows with a sparse list (any L: the variant that masks positions past the end)");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   __shared__ int s_item;
 
@@ -205,6 +208,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
   const int u = (lane >> 4) & 1, kq = (lane & 15) >> 2, qq = lane & 3;
 
   float* bias = reinterpret_cast<float*>(smem + C::BIAS_OFF);
+  // per bias-ring slot: tile number + 1 of the last tile that put a key to be masked out into the slot
+  int* masked_tile = reinterpret_cast<int*>(smem + C::BIAS_OFF + C::NSTAGE * C::NT * 4);
   const unsigned lds0 = lds_address(smem);
 
   // ---- LDS layout: rows of ROWB bytes, 16-byte chunks XOR-swizzled so that reads are bank-conflict free ----
@@ -233,8 +238,15 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
 
   const unsigned k_rowb = (unsigned)(a.k_sl * 2), v_rowb = (unsigned)(a.v_sl * 2);
   const int N = DENSE ? 1 : a.N;
-  const bool short_group = !DENSE && (a.L % N) != 0;
+  constexpr bool short_group = NMODE == NMODE_GROUPS_SHORT;   // (the host picks the variant from L % N)
 
+  // Per bias-ring slot: the tile that was last consumed from it had masked keys, so its row holds entries other
+  // than zero and the next tile's loaders must rewrite it whole (true at the start: LDS holds anything).
+  bool slot_dirty[2] = {true, true};
+  // (this bookkeeping is used only where a short last group can put masked keys into any tile: N keys per group
+  // with L not a multiple of N; elsewhere only a ragged last tile has them, and every checked tile writes its
+  // whole row)
+  constexpr bool LAZY_BIAS = NMODE == NMODE_GROUPS_SHORT && !GROUPED;
   int iter = 0;
   for (;;) {
     // ---------------- fetch the next work item ----------------
@@ -314,6 +326,15 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     // a tile whose positions need a per-key entry in the bias row: short last group, ragged last tile, or (GROUPED)
     // always, since the row then carries the membership masks
     auto tile_needs_check = [&](int T) { return GROUPED || short_group || (T + 1) * C::NT > total; };
+    // ... and whether the scores of tile T need the bias row at all: with a short last group only the tiles that
+    // contain it do, and the lanes that loaded its missing keys have said so in masked_tile (a stale entry of an
+    // earlier work item can only make a tile take the bias row needlessly: the row is written for every tile)
+    // (`entry` is masked_tile[T & 1], read by the caller early enough that its latency is hidden)
+    auto tile_has_masked_keys = [&](int T, int entry) {
+      if (GROUPED || (T + 1) * C::NT > total) return true;
+      if (!short_group) return false;
+      return __builtin_amdgcn_readfirstlane(entry) == T + 1;
+    };
     // full tiles with one key per group: one coalesced load per wave brings the RPW ids of its rows;
     // a cross-lane permute then hands each lane the id of its own row
     auto coalesced_ids = [&](int T) { return NMODE == NMODE_N1 && !tile_needs_check(T); };
@@ -337,7 +358,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         gi[i] = idx[min(grp, cnt - 1)];
         if constexpr (GROUPED) gm[i] = memb[min(grp, cnt - 1)];
       }
-      if (NMODE == NMODE_GROUPS && T < last) {   // a repeated (clamped) last tile must see the same tq, tr again
+      if ((NMODE == NMODE_GROUPS || NMODE == NMODE_GROUPS_SHORT) && T < last) {   // a repeated (clamped) last tile must see the same tq, tr again
         tq += a.nt_div_n;
         tr += a.nt_mod_n;
         if (tr >= N) {
@@ -355,21 +376,49 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         return;
       }
       const bool checked = tile_needs_check(T);
+      if constexpr (!LAZY_BIAS) {
+        // a checked tile writes its whole row (GROUPED: the membership masks, every tile)
+#pragma unroll
+        for (int i = 0; i < C::IPW; i++) {
+          const int p = T * C::NT + lpos + i * C::RPI;
+          int key = NMODE == NMODE_DENSE ? p : NMODE == NMODE_N1 ? gi[i] : gi[i] * N + wi[i];
+          if (__builtin_expect(checked, 0)) {
+            const bool ok = p < total && key < a.L;
+            key = ok ? key : 0;
+            if (pc == 0) {
+              if constexpr (GROUPED)
+                reinterpret_cast<int*>(bias)[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? gm[i] : 0;
+              else
+                bias[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? 0.0f : -INFINITY;
+            }
+          }
+          keyC[i] = key;
+        }
+        return;
+      }
+      // Bias row of the slot: 0 for a real key, -inf for a padded / out-of-range one.  A row is all zeros unless its
+      // tile had such keys; then the tile's consumers mark the slot dirty and the loaders of the next tile in it
+      // write every entry.  Otherwise only the (rare) -inf entries are written, and the tile is announced in
+      // masked_tile so that the consumers look at the row at all.
+      const bool rewrite = slot_dirty[T & 1];
+      bool ok[C::IPW];
+      bool any_bad = false;
 #pragma unroll
       for (int i = 0; i < C::IPW; i++) {
         const int p = T * C::NT + lpos + i * C::RPI;
-        int key = NMODE == NMODE_DENSE ? p : NMODE == NMODE_N1 ? gi[i] : gi[i] * N + wi[i];
-        if (__builtin_expect(checked, 0)) {
-          const bool ok = p < total && key < a.L;
-          key = ok ? key : 0;
-          if (pc == 0) {
-            if constexpr (GROUPED)
-              reinterpret_cast<int*>(bias)[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? gm[i] : 0;
-            else
-              bias[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? 0.0f : -INFINITY;
-          }
+        int key = gi[i] * N + wi[i];
+        ok[i] = !checked || (p < total && key < a.L);
+        any_bad |= !ok[i];
+        keyC[i] = ok[i] ? key : 0;
+      }
+      if (__builtin_expect(rewrite || __builtin_amdgcn_ballot_w64(any_bad) != 0, 0)) {
+        if (pc == 0) {
+#pragma unroll
+          for (int i = 0; i < C::IPW; i++)
+            if (rewrite || !ok[i]) bias[(T & 1) * C::NT + lpos + i * C::RPI] = ok[i] ? 0.0f : -INFINITY;
         }
-        keyC[i] = key;
+        if (any_bad) masked_tile[T & 1] = T + 1;
+        slot_dirty[T & 1] = false;   // (a row left alone by unchecked tiles stays dirty until a tile rewrites it)
       }
     };
     // LDS: K ring slots 0,1 then V ring slots 0,1, TENSOR_BYTES each.  A run of up to four gathers of one wave
@@ -500,6 +549,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
                         auto with_mfma) {
       constexpr bool EXP = decltype(with_exp)::value;
       constexpr bool MFMA = decltype(with_mfma)::value;
+      // written before the barrier that precedes this phase; consumed at its end
+      const int masked_entry = LAZY_BIAS ? masked_tile[Tm & 1] : 0;
       if constexpr (PART == PART_GATHER) {   // only the bookkeeping the gathers depend on
 #pragma unroll
         for (int i = 0; i < C::IPW; i++) {
@@ -565,10 +616,13 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         keyB[i] = keyC[i];
       }
       float m_new;
-      if (__builtin_expect(tile_needs_check(Tm), 0))
+      // (the same in every wave of the workgroup)
+      const bool masked = LAZY_BIAS ? tile_has_masked_keys(Tm, masked_entry) : tile_needs_check(Tm);
+      if (__builtin_expect(masked, 0))
         softmax_max<true>(Sn, bias + (Tm & 1) * C::NT + kw * 32, g, m_pend, m_new, GROUPED ? my_member : -1);
       else
         softmax_max<false>(Sn, nullptr, g, m_pend, m_new);
+      if constexpr (LAZY_BIAS) slot_dirty[Tm & 1] |= masked;
       m_pend = m_new;
       const bool lane_moves = (m_run == -INFINITY) ? (m_new > m_run) : ((m_new - m_run) * a.c_log2 > kLazyLog2);
       resc = __builtin_amdgcn_ballot_w64(lane_moves) != 0;
