@@ -224,3 +224,30 @@ def test_zero_query_closed_form_is_exact():
         mean = vi[keys].sum(0) / keys.size
         np.testing.assert_allclose(lse[0, s, r0:r1], np.log(keys.size), rtol=0, atol=2e-6 * np.log(keys.size) + 1e-6)
         assert np.all(np.abs(out[0, s, r0:r1] - mean) <= np.abs(mean) * 2.0 ** -8 + 1e-30)
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for c in range(n):
+        M = int(rng.choice([16, 32, 64, 128]))
+        d = int(rng.choice([64, 128]))
+        N = int(rng.choice([1, 1, 2, 4, 8, 12, 16, 32, 33, 64, 100, 128]))
+        L = int(rng.integers(1, 1800))
+        H = int(rng.integers(1, 4))
+        kind = [W.MASK_RANDOM, W.MASK_SKEW_LEN][int(rng.integers(0, 2))]
+        density = float(rng.choice([0.05, 0.3, 0.6, 1.0]))
+        cases.append((M, N, d, L, H, kind, density, 9000 + c))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,d,L,H,kind,density,seed", _random_cases(24, 20250927))
+def test_seeded_random_shapes(oracle_mod, M, N, d, L, H, kind, density, seed):
+    """Shapes nobody picked by hand: tile size, group size (also not a power of two, larger than L), length, head
+    count, list-length skew and density drawn from a fixed seed; every row against the oracle."""
+    w = small(M, N, d, L=L, H=H, kind=kind, density=density, seed=seed, skew=0.8)
+    say("random shape %s H=%d kind=%d density=%.2f" % (w.name, H, kind, density))
+    prob = Problem(w)
+    p = prob.params()
+    assert F.fgattn_validate_mask(prob.d_indptr, prob.d_indices, p, prob.workspace(p)) == 0
+    check_against_oracle(oracle_mod, prob, prob.run(), what=w.name)
