@@ -240,3 +240,33 @@ def test_mask_full_size_hunyuan(oracle_mod):
                   set(rng.choice(w.items, size=11, replace=False).tolist()))
     bad = check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, what=w.name)
     assert bad <= 2
+
+
+def _random_mask_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for c in range(n):
+        M = int(rng.choice([16, 32, 64, 128]))
+        d = int(rng.choice([64, 128]))
+        N = int(rng.choice([1, 1, 2, 3, 8, 17, 32, 64]))
+        L = int(rng.integers(8, 2500))
+        H = int(rng.integers(1, 4))
+        top_p = float(rng.choice([0.3, 0.7, 0.9, 0.99]))
+        gain = float(rng.choice([0.0, 1.0, 2.0]))
+        cases.append((M, N, d, L, H, top_p, gain, 4700 + c))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,d,L,H,top_p,gain,seed", _random_mask_cases(16, 20250928))
+def test_mask_seeded_random_shapes(oracle_mod, M, N, d, L, H, top_p, gain, seed):
+    # shapes nobody picked by hand, drawn from a fixed seed; every query block against the oracle
+    w = W.Workload("mask-rand-M%d-N%d-d%d-L%d" % (M, N, d, L), H=H, L=L, d=d, M=M, N=N, grid=(1, 1, L), seed=seed)
+    if gain > 0.0:
+        q, k = W.make_qk_local(w, gain=gain, bandwidth=0.02)
+    else:
+        q, k, _ = W.make_qkv(w)
+    say("mask %s H=%d p=%.2f gain=%.1f" % (w.name, H, top_p, gain))
+    indptr, indices, pooled = gpu_mask(w, q, k, top_p, want_pooled=True)
+    assert np.array_equal(pooled, oracle_mod.pool(q, M)), "query block means differ from the oracle's bits"
+    bad = check_rows(oracle_mod, w, q, k, top_p, indptr, indices, list(range(w.items)), what=w.name)
+    assert bad <= max(1, w.items // 20)
