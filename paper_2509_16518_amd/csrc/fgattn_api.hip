@@ -346,6 +346,8 @@ int fgattn_grid_size(const fgattn_params* p) {
   fg::FwdArgs a;
   memset(&a, 0, sizeof(a));
   a.M = p->M;
+  a.N = p->N;
+  a.L = p->L;
   a.n_items = (int32_t)fg::n_items_of(p);
   a.indptr = reinterpret_cast<const int64_t*>(&a);   // any non-null value: report the sparse variant's grid
   int grid = 0;

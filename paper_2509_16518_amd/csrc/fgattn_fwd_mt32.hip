@@ -15,7 +15,7 @@ static int launch_d(const FwdArgs& a, int cus, hipStream_t stream, int* grid_onl
     return launch_variant(fgattn_fwd_kernel<32, D, NMODE_DENSE, OCC>, lds, a, cus, stream, grid_only, occ[0]);
   if (a.N == 1)
     return launch_variant(fgattn_fwd_kernel<32, D, NMODE_N1, OCC>, lds, a, cus, stream, grid_only, occ[1]);
-  if (a.L % a.N == 0)
+  if (a.N > 0 && a.L % a.N == 0)
     return launch_variant(fgattn_fwd_kernel<32, D, NMODE_GROUPS, OCC>, lds, a, cus, stream, grid_only, occ[2]);
   return launch_variant(fgattn_fwd_kernel<32, D, NMODE_GROUPS_SHORT, OCC>, lds, a, cus, stream, grid_only, occ[3]);
 }

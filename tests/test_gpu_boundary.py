@@ -86,3 +86,11 @@ def test_forward_part_is_a_measurement_aid_only(M):
     a = prob.out.clone()
     got = prob.run()
     assert torch.equal(a, prob.out)
+
+
+@pytest.mark.parametrize("M,N,L", [(64, 1, 32760), (128, 32, 32760), (128, 32, 32768), (16, 8, 1000)])
+def test_grid_size_is_reported_for_every_variant(M, N, L):
+    q = torch.empty((1, 2, L, 128), dtype=torch.bfloat16, device="cuda")
+    p = F.make_params(q, q, q, q, M, N, 0.1)
+    grid = F.lib().fgattn_grid_size(ctypes.byref(p))
+    assert 1 <= grid <= 4096
