@@ -24,7 +24,7 @@ sys.path.insert(0, REPO)
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 # HBM bytes per launch of the forward kernel on the wan-1.3b workload, from the FETCH_SIZE / WRITE_SIZE
 # rocprofv3 runs summarised in profiles/fgattn_fwd_kernel_wan-1.3b.md (scaled by the copy-kernel factors there)
-HBM_TRAFFIC_BYTES = {"wan-1.3b": 3.23e9}
+HBM_TRAFFIC_BYTES = {"wan-1.3b": 2.06e9}
 
 
 def log(msg):
