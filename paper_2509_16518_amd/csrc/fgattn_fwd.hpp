@@ -352,9 +352,10 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
           grp = T * C::NT + lpos + i * C::RPI;
         } else {
           const int x = tr + lpos + i * C::RPI;          // < N + NT
-          const int q = N >= C::NT ? (x >= N ? 1 : 0) : (int)(((unsigned)x * a.n_recip16) >> 16);
+          // (24-bit multiplies, which run at full rate: x < 2 NT and the reciprocal has 17 bits; below, q N <= x)
+          const int q = N >= C::NT ? (x >= N ? 1 : 0) : (int)(__umul24((unsigned)x, a.n_recip16) >> 16);
           grp = tq + q;
-          wi[i] = x - q * N;
+          wi[i] = x - (int)__umul24((unsigned)q, (unsigned)N);
         }
         gi[i] = idx[min(grp, cnt - 1)];
         if constexpr (GROUPED) gm[i] = memb[min(grp, cnt - 1)];
@@ -382,7 +383,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
 #pragma unroll
         for (int i = 0; i < C::IPW; i++) {
           const int p = T * C::NT + lpos + i * C::RPI;
-          int key = NMODE == NMODE_DENSE ? p : NMODE == NMODE_N1 ? gi[i] : gi[i] * N + wi[i];
+          // (group id and N are below 2^24 and so is their product, a key row)
+          int key = NMODE == NMODE_DENSE ? p : NMODE == NMODE_N1 ? gi[i] : (int)__umul24((unsigned)gi[i], (unsigned)N) + wi[i];
           if (__builtin_expect(checked, 0)) {
             const bool ok = p < total && key < a.L;
             key = ok ? key : 0;
@@ -407,7 +409,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
 #pragma unroll
       for (int i = 0; i < C::IPW; i++) {
         const int p = T * C::NT + lpos + i * C::RPI;
-        int key = gi[i] * N + wi[i];
+        int key = (int)__umul24((unsigned)gi[i], (unsigned)N) + wi[i];
         ok[i] = !checked || (p < total && key < a.L);
         any_bad |= !ok[i];
         keyC[i] = ok[i] ? key : 0;
