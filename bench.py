@@ -191,6 +191,14 @@ def main():
         res["dense"] = {"ms": ms_dense, "tflops": dense_flop / ms_dense / 1e9,
                         "pct_bf16_mfma_peak": 100.0 * dense_flop / ms_dense / 1e9 / MFMA_BF16_PEAK_TFLOPS, "steps": nd}
         res["sparse_over_dense_time"] = ms_step / ms_dense
+        if w.M != 128:
+            # the dense kernel does not depend on the mask's tile size: also time it with 128-row query tiles,
+            # its fastest tiling, so that the sparse step is also compared with the best dense kernel of this build
+            p128 = F.make_params(dq, dk, dv, out, 128, 1, w.scale)
+            ws128 = torch.empty(F.fgattn_workspace_bytes(p128), dtype=torch.uint8, device="cuda")
+            ms_d128 = time_calls(lambda: F.fgattn_dense_forward(dq, dk, dv, p128, out, lse, ws128), 2, nd)
+            res["dense_128_row_tiles"] = {"ms": ms_d128, "tflops": dense_flop / ms_d128 / 1e9,
+                                          "sparse_over_dense_time": ms_step / ms_d128}
         if "mask" in res:
             res["mask"]["over_dense_time"] = (res["mask"]["select_ms"] + res["mask"]["emit_ms"]) / ms_dense
     if args.cpu_items > 0:
