@@ -270,3 +270,13 @@ def test_mask_seeded_random_shapes(oracle_mod, M, N, d, L, H, top_p, gain, seed)
     assert np.array_equal(pooled, oracle_mod.pool(q, M)), "query block means differ from the oracle's bits"
     bad = check_rows(oracle_mod, w, q, k, top_p, indptr, indices, list(range(w.items)), what=w.name)
     assert bad <= max(1, w.items // 20)
+
+
+@pytest.mark.parametrize("M,N,L,top_p", [(64, 64, 8, 0.9), (16, 128, 130, 0.5), (128, 1, 1, 1.0), (32, 1, 2, 0.99), (16, 1, 33, 1.0)])
+def test_mask_degenerate_sizes(oracle_mod, M, N, L, top_p):
+    # one or two key blocks, a single token, fewer tokens than one query block, p = 1
+    w = W.Workload("mask-degenerate-M%d-N%d-L%d" % (M, N, L), H=2, L=L, d=64, M=M, N=N, seed=4900 + L)
+    q, k, _ = W.make_qkv(w)
+    say("mask %s p=%.2f" % (w.name, top_p))
+    indptr, indices = gpu_mask(w, q, k, top_p)
+    check_rows(oracle_mod, w, q, k, top_p, indptr, indices, list(range(w.items)), what=w.name)
