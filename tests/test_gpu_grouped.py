@@ -139,6 +139,21 @@ def test_device_grouping_with_batch(oracle_mod):
         check_against_oracle(oracle_mod, prob, out, what=w.name + " " + mode)
 
 
+@pytest.mark.parametrize("M,N,L", [(16, 1, 40), (16, 1, 16), (32, 8, 33), (64, 1, 200)])
+def test_device_grouping_degenerate_sizes(oracle_mod, M, N, L):
+    # fewer tiles than a group holds, a single tile, a single-row last tile, one group per slice plus a remainder
+    w = W.Workload("group-degenerate-M%d-N%d-L%d" % (M, N, L), H=2, L=L, d=64, M=M, N=N, kind=W.MASK_RANDOM,
+                   density=0.5, seed=6600 + L)
+    prob = Problem(w)
+    for mode in ("xor", "consecutive"):
+        got = gpu_grouping(prob, mode)
+        ref = GR.grouped_mask(prob.indptr, prob.indices, w.H, w.QB, w.G, 128 // M, mode)
+        for a, b, name in zip(got, ref, ("group_tiles", "union_indptr", "union_indices", "union_members")):
+            assert np.array_equal(a, b), name + " " + mode
+        out = run_grouped(prob, *got)
+        check_against_oracle(oracle_mod, prob, out, what=w.name + " " + mode)
+
+
 def test_grouping_argument_checks():
     prob = Problem(W.TINY)
     p = prob.params()
