@@ -94,3 +94,36 @@ def test_grid_size_is_reported_for_every_variant(M, N, L):
     p = F.make_params(q, q, q, q, M, N, 0.1)
     grid = F.lib().fgattn_grid_size(ctypes.byref(p))
     assert 1 <= grid <= 4096
+
+
+def test_forward_is_graph_capturable():
+    # the library allocates nothing and clears no memory on the hot path: a call (ordering pre-pass + kernel) can be
+    # captured into a graph; every replay must reproduce the eager result bit for bit
+    w = W.Workload("graph", H=3, L=2048, d=128, M=64, N=1, kind=W.MASK_SKEW_LEN, density=0.3, skew=0.7, seed=5200)
+    prob = Problem(w)
+    p = prob.params()
+    ws = prob.workspace(p)
+    F.fgattn_forward(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, prob.out, prob.lse, ws)   # also warms caches
+    torch.cuda.synchronize()
+    ref_out, ref_lse = prob.out.clone(), prob.lse.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        F.fgattn_forward(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, prob.out, prob.lse, ws)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            F.fgattn_forward(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, prob.out, prob.lse, ws)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        prob.out.view(torch.int16).fill_(0x7FC0)
+        prob.lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(prob.out.view(torch.int16), ref_out.view(torch.int16)), "replay %d: out differs" % replay
+        assert torch.equal(prob.lse, ref_lse), "replay %d: lse differs" % replay
+        # eager work between the replays
+        F.fgattn_forward(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, prob.out, prob.lse, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(prob.out.view(torch.int16), ref_out.view(torch.int16))
