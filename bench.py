@@ -76,8 +76,8 @@ def main():
                     help="also run a plain 256 MiB device copy kernel (reference for scaling rocprofv3 FETCH/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (heads and query blocks shard with no "
-              "exchange; see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py measures one GPU: this build has no multi-GPU path (heads and query blocks are independent, "
+              "so they would shard across GPUs with no exchange step). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
