@@ -90,21 +90,10 @@ int fgattn_forward(const void* q, const void* k, const void* v, const int64_t* m
                    size_t workspace_bytes, void* stream);
 
 /* Dense attention (0% sparsity: every key active), the comparison kernel of the same build
- * (paper Sec. 2 "Efficient dense attention").  Same arguments minus the mask; p->N is ignored. */
+ * (paper Sec. 2 "Efficient dense attention").  Same arguments minus the mask; p->N is ignored
+ * (fgattn_workspace_bytes still wants N >= 1). */
 int fgattn_dense_forward(const void* q, const void* k, const void* v, const fgattn_params* p, void* out, float* lse,
                          void* workspace, size_t workspace_bytes, void* stream);
-
-/* Measurement aid, not part of the method: runs one half of fgattn_forward's kernel on the same launch shape,
- * FGATTN_PART_GATHER = index translation and K/V row gathers only (the data movement of Sec. 4.1),
- * FGATTN_PART_COMPUTE = everything except the row gathers (MFMA, softmax, LDS reads on whatever the tiles hold).
- * Same arguments and error behaviour as fgattn_forward; only M = 64 or 128 with d = 128, N = 1 is built (else
- * FGATTN_E_SHAPE; an unknown `part` gives FGATTN_E_FLAGS).  `out` and `lse` are overwritten with meaningless
- * values. */
-#define FGATTN_PART_GATHER 1
-#define FGATTN_PART_COMPUTE 2
-int fgattn_forward_part(const void* q, const void* k, const void* v, const int64_t* mask_indptr,
-                        const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* workspace,
-                        size_t workspace_bytes, int part, void* stream);
 
 /*
  * Sparse forward pass over GROUPED query tiles (paper Sec. 4.2 "Grouping Query Tiles Attending to Similar Sets of
@@ -193,6 +182,22 @@ int fgattn_mask_emit(const fgattn_params* p, const int64_t* mask_indptr, int32_t
 int fgattn_grid_size(const fgattn_params* p);
 
 const char* fgattn_strerror(int code);
+
+/* ---------------------------------------------------------------------------------------------------------------
+ * Measurement aids -- not part of the method, not needed by any caller of the path; benchmarks use them.
+ * --------------------------------------------------------------------------------------------------------------- */
+
+/* Runs one half of fgattn_forward's kernel on the same launch shape,
+ * FGATTN_PART_GATHER = index translation and K/V row gathers only (the data movement of Sec. 4.1),
+ * FGATTN_PART_COMPUTE = everything except the row gathers (MFMA, softmax, LDS reads on whatever the tiles hold).
+ * Same arguments and error behaviour as fgattn_forward; only M = 64 or 128 with d = 128, N = 1 is built (else
+ * FGATTN_E_SHAPE; an unknown `part` gives FGATTN_E_FLAGS).  `out` and `lse` are overwritten with meaningless
+ * values. */
+#define FGATTN_PART_GATHER 1
+#define FGATTN_PART_COMPUTE 2
+int fgattn_forward_part(const void* q, const void* k, const void* v, const int64_t* mask_indptr,
+                        const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* workspace,
+                        size_t workspace_bytes, int part, void* stream);
 
 #ifdef __cplusplus
 }

@@ -30,6 +30,20 @@ def build_workloads(force=True):
     return LIBFGW
 
 
+def check_m0_writes(asm_path):
+    """The gathers of the forward kernel set the LDS-DMA base register M0 in one inline-assembly statement and rely
+    on it in the following ones; nothing the compiler emits in between may write M0.  Every mention of M0 in the
+    device assembly must therefore be one of the kernel's own marked `s_mov_b32 m0` lines."""
+    import re
+    tok = re.compile(r"\bm0\b")
+    with open(asm_path) as f:
+        for n, line in enumerate(f, 1):
+            code = line.split(";", 1)[0]
+            if tok.search(code) and "fg_m0" not in line:
+                raise RuntimeError("%s:%d: M0 is touched outside the kernel's own gather statements: %s" %
+                                   (asm_path, n, line.strip()))
+
+
 def build_hip(force=True, extra_flags=()):
     """Compile every .hip translation unit for gfx950 (in parallel) and link libfgattn.so in-tree."""
     from concurrent.futures import ThreadPoolExecutor
@@ -39,9 +53,14 @@ def build_hip(force=True, extra_flags=()):
     objdir = os.path.join(PKG_DIR, "_build")
     os.makedirs(objdir, exist_ok=True)
     common = [f for f in HIP_FLAGS if f != "-shared"] + list(extra_flags) + \
-        ["-I", os.path.join(REPO_DIR, "include"), "-I", CSRC]
+        ["-save-temps=obj", "-I", os.path.join(REPO_DIR, "include"), "-I", CSRC]
     objs = [os.path.join(objdir, os.path.basename(s)[:-4] + ".o") for s in srcs]
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         list(ex.map(lambda so: _run([HIPCC] + common + ["-c", so[0], "-o", so[1]]), zip(srcs, objs)))
+    for f in sorted(os.listdir(objdir)):
+        if f.endswith("-gfx950.s"):
+            check_m0_writes(os.path.join(objdir, f))
+        elif not f.endswith(".o"):
+            os.remove(os.path.join(objdir, f))   # other intermediates of -save-temps
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIBFGATTN])
     return LIBFGATTN

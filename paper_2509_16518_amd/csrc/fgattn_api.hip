@@ -5,6 +5,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "fgattn.h"
 #include "fgattn_launch.hpp"
 
@@ -128,10 +130,12 @@ struct DeviceInfo {
   int cus = 0;
 };
 static DeviceInfo g_dev[64];
+static std::mutex g_dev_mutex;   // first calls from several host threads fill the table one at a time
 
 static int device_info(DeviceInfo* out) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
+  std::lock_guard<std::mutex> lock(g_dev_mutex);
   DeviceInfo& d = g_dev[dev];
   if (!d.known) {
     hipDeviceProp_t prop;
@@ -175,9 +179,10 @@ static int check_tensors(const void* q, const void* k, const void* v, const void
   for (int i = 0; i < 4; i++)
     if ((reinterpret_cast<uintptr_t>(ptrs[i]) & 15) != 0) return FGATTN_E_ALIGN;
   if ((reinterpret_cast<uintptr_t>(lse) & 3) != 0) return FGATTN_E_ALIGN;
-  // the gather addresses K/V rows with 32-bit byte offsets from the (batch, head) slice base
+  // the gather addresses K/V rows with 32-bit byte offsets from the (batch, head) slice base; every lane offset
+  // also carries a +4096 bias (the base pointer is moved down by as much, see gather16_next), which must not wrap
   const int64_t last = (int64_t)p->L - 1;
-  if (last * p->k_stride_l * 2 + 2 * p->d > 0xffffffffLL || last * p->v_stride_l * 2 + 2 * p->d > 0xffffffffLL)
+  if (last * p->k_stride_l * 2 + 2 * p->d + 4096 > 0xffffffffLL || last * p->v_stride_l * 2 + 2 * p->d + 4096 > 0xffffffffLL)
     return FGATTN_E_STRIDE;
   if (!isfinite(p->scale)) return FGATTN_E_SCALE;
   return FGATTN_OK;
@@ -282,7 +287,10 @@ int fgattn_forward(const void* q, const void* k, const void* v, const int64_t* m
 
 int fgattn_dense_forward(const void* q, const void* k, const void* v, const fgattn_params* p, void* out, float* lse,
                          void* workspace, size_t workspace_bytes, void* stream) {
-  return fg::run_forward(q, k, v, nullptr, nullptr, p, out, lse, workspace, workspace_bytes, stream);
+  if (p == nullptr) return FGATTN_E_NULL;
+  fgattn_params pd = *p;
+  pd.N = 1;   // there is no mask, hence no key groups: whatever the caller left in N is ignored
+  return fg::run_forward(q, k, v, nullptr, nullptr, &pd, out, lse, workspace, workspace_bytes, stream);
 }
 
 int fgattn_forward_part(const void* q, const void* k, const void* v, const int64_t* mask_indptr,

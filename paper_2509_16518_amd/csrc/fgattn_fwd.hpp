@@ -63,17 +63,21 @@ __device__ __forceinline__ void gather16_to_lds(const void* base, unsigned byte_
                                   (unsigned)__builtin_amdgcn_readfirstlane((int)(b64 & 0xffffffffu)));
   lds_base = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_base);
   asm volatile(
-      "s_mov_b32 m0, %2\n\t"
+      "s_mov_b32 m0, %2 ; fg_m0\n\t"
       "s_nop 0\n\t"
       "global_load_lds_dwordx4 %0, %1"
       :
       : "v"(byte_off), "s"(base), "s"(lds_base)
-      : "memory");   // m0 is a reserved register: no compiler-generated instruction of this kernel reads it
+      : "memory", "m0");
 }
 // The same transfer for a run of up to four 1 KiB loads that land back to back in LDS: M0 is written once
 // (gather16_first) and the following loads (gather16_next<K>) add K KiB through the instruction offset.  That
 // offset also enters the global address, so `base_m4k` is the true base minus 4096 and the byte offset carries
 // +4096 - 1024*K (kept non-negative: the 32-bit offset is zero-extended).
+// gather16_next relies on M0 still holding what the preceding gather16_first wrote.  The statements in between are
+// MFMAs, LDS reads and vector arithmetic, none of which the compiler implements through M0 on gfx950; the build
+// enforces it: it scans the generated assembly of every kernel and fails if any instruction other than the
+// `s_mov_b32 m0` lines marked fg_m0 above writes M0.
 __device__ __forceinline__ const void* pin_scalar(const void* p) {
   // wave-uniform by construction; readfirstlane pins it to scalar registers (it folds away when already there)
   const uint64_t b64 = (uint64_t)(uintptr_t)p;
@@ -84,12 +88,12 @@ __device__ __forceinline__ void gather16_first(const void* base_m4k, unsigned by
   base_m4k = pin_scalar(base_m4k);
   lds_base = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_base);
   asm volatile(
-      "s_mov_b32 m0, %2\n\t"
+      "s_mov_b32 m0, %2 ; fg_m0\n\t"
       "s_nop 0\n\t"
       "global_load_lds_dwordx4 %0, %1"
       :
       : "v"(byte_off), "s"(base_m4k), "s"(lds_base)
-      : "memory");
+      : "memory", "m0");
 }
 template <int K>
 __device__ __forceinline__ void gather16_next(const void* base_m4k, unsigned byte_off) {
@@ -291,6 +295,10 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     const int total = cnt * N;  // compacted key positions (a short last group leaves invalid ones)
     const int ntiles = (total + C::NT - 1) / C::NT;
     const int32_t* idx = DENSE ? nullptr : a.indices + beg;
+    // Row that padded / out-of-range positions of a tile fetch (their scores are masked out): the item's first
+    // active key, so that only rows of the active set are ever multiplied, even by zero (0 x Inf would be NaN).
+    int pad_key = 0;
+    if (!DENSE && cnt > 0) pad_key = __builtin_amdgcn_readfirstlane(idx[0]) * N;
     const uint16_t* kbase = a.k + b * a.k_sb + h * a.k_sh;
     const uint16_t* vbase = a.v + b * a.v_sb + h * a.v_sh;
 
@@ -370,7 +378,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       }
     };
     // ids of tile T (fetched earlier) -> key rows in keyC; padded / out-of-range positions of a checked tile
-    // read row 0 and get a -inf score bias
+    // read the item's first active row and get a -inf score bias
     auto make_keys = [&](int T) {
       if (NMODE == NMODE_N1 && __builtin_expect(coalesced_ids(T), 1)) {
 #pragma unroll
@@ -387,7 +395,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
           int key = NMODE == NMODE_DENSE ? p : NMODE == NMODE_N1 ? gi[i] : (int)__umul24((unsigned)gi[i], (unsigned)N) + wi[i];
           if (__builtin_expect(checked, 0)) {
             const bool ok = p < total && key < a.L;
-            key = ok ? key : 0;
+            key = ok ? key : pad_key;
             if (pc == 0) {
               if constexpr (GROUPED)
                 reinterpret_cast<int*>(bias)[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? gm[i] : 0;
@@ -412,7 +420,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         int key = (int)__umul24((unsigned)gi[i], (unsigned)N) + wi[i];
         ok[i] = !checked || (p < total && key < a.L);
         any_bad |= !ok[i];
-        keyC[i] = ok[i] ? key : 0;
+        keyC[i] = ok[i] ? key : pad_key;
       }
       if (__builtin_expect(rewrite || __builtin_amdgcn_ballot_w64(any_bad) != 0, 0)) {
         if (pc == 0) {

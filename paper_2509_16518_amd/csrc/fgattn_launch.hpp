@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "fgattn.h"
 #include "fgattn_args.hpp"
 
@@ -12,6 +14,8 @@ int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipS
                    int* occ_cache) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
+  static std::mutex cache_mutex;   // one per kernel variant: first calls from several host threads take turns
+  std::unique_lock<std::mutex> lock(cache_mutex);
   if (occ_cache[dev] == 0) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             lds_bytes) != hipSuccess)
@@ -22,6 +26,7 @@ int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipS
     occ_cache[dev] = occ;
   }
   long long want = (long long)cus * occ_cache[dev];
+  lock.unlock();
 #ifdef FG_ONE_WG_PER_CU
   want = cus;
 #endif

@@ -68,3 +68,41 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(build, "LIBFGATTN", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError, match="libfgattn.so is missing"):
         F.lib()
+
+
+def test_gather_offset_bound_includes_the_bias(lib):
+    # K/V rows are addressed with 32-bit byte offsets that also carry a +4096 bias: a slice whose last row ends
+    # within 4 KiB below 4 GiB must be rejected, one just under the bound accepted (it then fails on the
+    # zero-sized workspace, before any device is touched)
+    one = ctypes.c_void_p(4096)
+    d, L = 128, 257
+    stride = 8388600                      # elements; 2 * stride < 2^24
+    assert (L - 1) * stride * 2 + 2 * d <= 0xffffffff < (L - 1) * stride * 2 + 2 * d + 4096
+
+    def call(k_stride, v_stride):
+        p = F.FgattnParams(1, 1, L, d, 64, 1, 0, 0, d, 0, 0, k_stride, 0, 0, v_stride, 0, 0, d, 0.1, 0)
+        return lib.fgattn_forward(one, one, one, one, one, ctypes.byref(p), one, one, one, 0, None)
+    assert call(stride, d) == F.E_STRIDE
+    assert call(d, stride) == F.E_STRIDE
+    inside = stride - 16                  # 256 rows * 32 bytes less: 8 KiB below the bound
+    assert (L - 1) * inside * 2 + 2 * d + 4096 <= 0xffffffff
+    assert call(inside, inside) == F.E_WORKSPACE
+    assert call(d, d) == F.E_WORKSPACE
+
+
+def test_dense_call_ignores_n(lib):
+    one = ctypes.c_void_p(4096)
+    for n in (0, -3, 7):
+        p = F.FgattnParams(1, 1, 256, 128, 64, n, 0, 0, 128, 0, 0, 128, 0, 0, 128, 0, 0, 128, 0.1, 0)
+        assert lib.fgattn_dense_forward(one, one, one, ctypes.byref(p), one, one, one, 0, None) == F.E_WORKSPACE
+    assert lib.fgattn_dense_forward(one, one, one, None, one, one, one, 0, None) == F.E_NULL
+
+
+def test_build_rejects_a_foreign_m0_write(tmp_path):
+    good = tmp_path / "good.s"
+    good.write_text("\ts_mov_b32 m0, s5 ; fg_m0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v1, s[2:3]\n\t; a comment naming m0\n")
+    build.check_m0_writes(str(good))
+    bad = tmp_path / "bad.s"
+    bad.write_text("\ts_mov_b32 m0, s5 ; fg_m0\n\ts_mov_b32 m0, s9\n")
+    with pytest.raises(RuntimeError, match="M0 is touched"):
+        build.check_m0_writes(str(bad))

@@ -20,6 +20,10 @@ from gpu_util import Problem, check_against_oracle, say, to_dev_bf16
 
 pytestmark = pytest.mark.gpu
 EPS = 1e-5
+# Query blocks per test case (keyed by the label and p) whose kept set differed from the oracle's inside the
+# rounding allowance above, as observed on the GPU.  Every case not listed has none and must stay at none: the
+# allowance exists for cumulative sums that pass p within EPS, and is not a blanket budget.
+OBSERVED_ROUNDING_ESCAPES = {}
 
 
 def gpu_mask(w, q_bits, k_bits, top_p, scale=None, want_pooled=False, flags=0):
@@ -67,6 +71,8 @@ def check_rows(oracle, w, q_bits, k_bits, top_p, indptr, indices, rows, scale=No
         assert ok, "%s row %d: kept %d (oracle %d), mass %.9f, least kept %.3e, best dropped %.3e" % (
             what, row, got.size, kept, mass, lo_in, hi_out)
     say("    %s: %d rows checked, %d differ within rounding of p" % (what, len(rows), inexact))
+    key = "%s p=%g" % (what, top_p)
+    assert inexact == OBSERVED_ROUNDING_ESCAPES.get(key, 0), "%s: %d query blocks used the rounding allowance" % (key, inexact)
     return inexact
 
 
@@ -83,7 +89,6 @@ def test_mask_matches_oracle_small(oracle_mod, M, N, d, L, grid, top_p, flags):
     assert np.array_equal(pooled, oracle_mod.pool(q, M)), "query block means differ from the oracle's bits"
     rows = list(range(w.items))
     bad = check_rows(oracle_mod, w, q, k, top_p, indptr, indices, rows, what=w.name)
-    assert bad <= max(1, len(rows) // 20)
     density = indices.size / float(w.items * w.G)
     say("    density %.3f" % density)
 
@@ -140,7 +145,6 @@ def test_mask_rows_longer_than_lds(oracle_mod):
     indptr, indices = gpu_mask(w, q, k, 0.9)
     rows = list(range(0, w.items, 13)) + [w.items - 1]
     bad = check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, what=w.name)
-    assert bad <= 2
     say("    density %.3f" % (indices.size / float(w.items * w.G)))
 
 
@@ -166,7 +170,6 @@ def test_mask_batch_and_strided_layout(oracle_mod, N):
     pooled = ws[:rows * w.d * 2].view(torch.int16).cpu().numpy().view(np.uint16).reshape(w.B * w.H, w.QB, w.d)
     assert np.array_equal(pooled, oracle_mod.pool(q, w.M)), "query block means differ from the oracle's bits"
     bad = check_rows(oracle_mod, w, q, k, 0.8, indptr.cpu().numpy(), indices.cpu().numpy(), list(range(rows)), what=w.name)
-    assert bad <= 2
 
 
 def test_mask_feeds_forward(oracle_mod):
@@ -218,7 +221,6 @@ def test_mask_full_size_wan(oracle_mod):
     rows = sorted({0, w.QB - 1, w.items - 1, int(np.argmax(nnz)), int(np.argmin(nnz))} |
                   set(rng.choice(w.items, size=43, replace=False).tolist()))
     bad = check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, what=w.name)
-    assert bad <= 5
 
 
 def test_mask_full_size_hunyuan(oracle_mod):
@@ -239,7 +241,6 @@ def test_mask_full_size_hunyuan(oracle_mod):
     rows = sorted({0, w.QB - 1, w.items - 1, int(np.argmax(nnz)), int(np.argmin(nnz))} |
                   set(rng.choice(w.items, size=11, replace=False).tolist()))
     bad = check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, what=w.name)
-    assert bad <= 2
 
 
 def _random_mask_cases(n, seed):
@@ -269,7 +270,6 @@ def test_mask_seeded_random_shapes(oracle_mod, M, N, d, L, H, top_p, gain, seed)
     indptr, indices, pooled = gpu_mask(w, q, k, top_p, want_pooled=True)
     assert np.array_equal(pooled, oracle_mod.pool(q, M)), "query block means differ from the oracle's bits"
     bad = check_rows(oracle_mod, w, q, k, top_p, indptr, indices, list(range(w.items)), what=w.name)
-    assert bad <= max(1, w.items // 20)
 
 
 @pytest.mark.parametrize("M,N,L,top_p", [(64, 64, 8, 0.9), (16, 128, 130, 0.5), (128, 1, 1, 1.0), (32, 1, 2, 0.99), (16, 1, 33, 1.0)])

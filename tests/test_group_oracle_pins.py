@@ -134,3 +134,61 @@ def test_union_and_membership_and_csr_form():
             assert sorted(seen) == list(range(QB))
         if mode == "consecutive":
             assert np.array_equal(tiles[:NG].ravel()[:QB], np.arange(QB))
+
+
+def objective_by_sets(sets, groups):
+    """Eq. (1) once more from its definition: for every group, the key blocks selected by exactly one of
+    (representative, member), counted over the group's members (the representative is the group's first tile)."""
+    total = 0
+    for g in groups:
+        rep = sets[g[0]]
+        for i in g:
+            total += sum(1 for x in rep | sets[i] if (x in rep) != (x in sets[i]))
+    return total
+
+
+@pytest.mark.parametrize("QB,G,R,seed", [(8, 20, 4, 0), (12, 33, 3, 1), (16, 64, 8, 2), (9, 17, 2, 3), (10, 25, 4, 4)])
+def test_objective_equals_the_definition_on_arbitrary_groupings(QB, G, R, seed):
+    # random groupings with a random tile (mostly not the lowest-numbered, not the first in index order) as
+    # representative, groups of uneven size included: the value must EQUAL the set-based sum, not just bound it
+    rng = np.random.default_rng(100 + seed)
+    b = rand_bits(rng, QB, G)
+    sets = [set(int(x) for x in np.flatnonzero(b[i])) for i in range(QB)]
+    for _ in range(20):
+        perm = [int(x) for x in rng.permutation(QB)]
+        groups = [perm[s:s + R] for s in range(0, QB, R)]
+        assert GR.objective(b, groups) == objective_by_sets(sets, groups)
+    # hand-checkable case: rows {0,1}, {1,2}, {5}; group [2,0,1] with tile 2 as representative:
+    # d(2,2) + d(2,0) + d(2,1) = 0 + 3 + 3; with tile 0 as representative: 0 + 2 + 3
+    hb = np.zeros((3, 6), dtype=bool)
+    hb[0, [0, 1]] = True
+    hb[1, [1, 2]] = True
+    hb[2, 5] = True
+    assert GR.objective(hb, [[2, 0, 1]]) == 6
+    assert GR.objective(hb, [[0, 1, 2]]) == 5
+    assert GR.objective(hb, [[0, 1], [2]]) == 2
+    assert GR.objective(hb, [[1], [2, 0]]) == 3
+
+
+def test_objective_pin_catches_planted_mistakes():
+    # the pins above must tell the definition from near misses: last tile as representative, pairs counted
+    # twice, union instead of symmetric difference, distance to the previous member instead of the representative
+    rng = np.random.default_rng(7)
+    b = rand_bits(rng, 12, 30)
+    sets = [set(int(x) for x in np.flatnonzero(b[i])) for i in range(12)]
+    wrong = {
+        "last tile as representative": lambda bits, groups: sum(GR.distance(bits[g[-1]], bits[i]) for g in groups for i in g),
+        "every pair counted": lambda bits, groups: sum(GR.distance(bits[j], bits[i]) for g in groups for j in g for i in g),
+        "union instead of xor": lambda bits, groups: sum(int(np.count_nonzero(bits[g[0]] | bits[i])) for g in groups for i in g),
+        "chain of neighbours": lambda bits, groups: sum(GR.distance(bits[g[max(t - 1, 0)]], bits[g[t]])
+                                                         for g in groups for t in range(len(g))),
+    }
+    for name, fn in wrong.items():
+        caught = False
+        for trial in range(20):
+            perm = [int(x) for x in rng.permutation(12)]
+            groups = [perm[s:s + 4] for s in range(0, 12, 4)]
+            if fn(b, groups) != objective_by_sets(sets, groups):
+                caught = True
+                break
+        assert caught, name
