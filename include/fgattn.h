@@ -39,7 +39,8 @@ enum {
   FGATTN_E_SCALE = -6,       /* scale is not finite */
   FGATTN_E_DEVICE = -7,      /* not a gfx950 device, or a HIP runtime call failed */
   FGATTN_E_MASK = -8,        /* fgattn_validate_mask found a bad mask */
-  FGATTN_E_FLAGS = -9        /* unknown flag bits */
+  FGATTN_E_FLAGS = -9,       /* unknown flag bits */
+  FGATTN_E_STATIC_LIMIT = -10 /* fgattn_forward_static: more work items than FGATTN_STATIC_MAX_ITEMS */
 };
 
 enum {
@@ -182,6 +183,21 @@ int fgattn_mask_emit(const fgattn_params* p, const int64_t* mask_indptr, int32_t
 int fgattn_grid_size(const fgattn_params* p);
 
 const char* fgattn_strerror(int code);
+
+/*
+ * Entry point for callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc).  Same computation, arguments, flags and error behaviour as
+ * fgattn_forward, minus the workspace: the work order and the queue counters live in a fixed array inside the
+ * library's device image (4 bytes per work item + 256 bytes; every GPU the library runs on holds its own copy
+ * until the process ends).  It calls no hipMalloc / hipFree and no allocating library routine.
+ *   limit : B * H * ceil(L/M) <= FGATTN_STATIC_MAX_ITEMS, else FGATTN_E_STATIC_LIMIT and nothing is enqueued;
+ *   all calls on one GPU share that GPU's array: calls that may overlap there (different streams, different host
+ *   threads) race -- order them on one stream; the array keeps the last call's contents, each call rebuilds what it
+ *   reads (FGATTN_FLAG_REUSE_PLAN reuses the order left by the previous call of THIS entry point on the same GPU).
+ */
+#define FGATTN_STATIC_MAX_ITEMS 65536
+int fgattn_forward_static(const void* q, const void* k, const void* v, const int64_t* mask_indptr,
+                          const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------------------------------------------
  * Measurement aids -- not part of the method, not needed by any caller of the path; benchmarks use them.

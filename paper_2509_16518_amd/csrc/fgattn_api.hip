@@ -269,6 +269,29 @@ static int run_forward(const void* q, const void* k, const void* v, const int64_
   return launch_forward(a, p->d, dev.cus, stream, nullptr);
 }
 
+// ------------------------------------------------------------------------------------------
+// Fixed scratch for fgattn_forward_static: the same layout as the caller-provided workspace
+// (int32 ctrl[64], then int32 order[n_items]) in the library's device image.  `scratch` is a
+// host-side stand-in for the symbol, not a device address: host code uses the per-device
+// address that hipGetSymbolAddress returns (each GPU holds its own copy at its own address).
+// ------------------------------------------------------------------------------------------
+static __device__ __align__(256) int32_t scratch[64 + FGATTN_STATIC_MAX_ITEMS];
+static void* g_scratch_ptr[64];   // per device, filled on the first call with that device current
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return FGATTN_E_DEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return FGATTN_OK;
+}
+
 }  // namespace fg
 
 extern "C" {
@@ -283,6 +306,22 @@ int fgattn_forward(const void* q, const void* k, const void* v, const int64_t* m
                    const fgattn_params* p, void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
   if (!mask_indptr || !mask_indices) return FGATTN_E_NULL;
   return fg::run_forward(q, k, v, mask_indptr, mask_indices, p, out, lse, workspace, workspace_bytes, stream);
+}
+
+int fgattn_forward_static(const void* q, const void* k, const void* v, const int64_t* mask_indptr,
+                          const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* stream) {
+  if (!mask_indptr || !mask_indices) return FGATTN_E_NULL;
+  int rc = fg::check_shape(p);
+  if (rc) return rc;
+  if (fg::n_items_of(p) > FGATTN_STATIC_MAX_ITEMS) return FGATTN_E_STATIC_LIMIT;
+  rc = fg::check_tensors(q, k, v, out, lse, p);
+  if (rc) return rc;
+  void* ws = nullptr;
+  rc = fg::static_scratch(&ws);
+  if (rc) return rc;
+  // the ordering pre-pass clears the queue counters itself (a kernel, no memset), so nothing else needs zeroing
+  return fg::run_forward(q, k, v, mask_indptr, mask_indices, p, out, lse, ws,
+                         sizeof(int32_t) * (64 + (size_t)FGATTN_STATIC_MAX_ITEMS), stream);
 }
 
 int fgattn_dense_forward(const void* q, const void* k, const void* v, const fgattn_params* p, void* out, float* lse,
@@ -375,6 +414,7 @@ const char* fgattn_strerror(int code) {
     case FGATTN_E_DEVICE: return "no gfx950 device current, or a HIP runtime call failed";
     case FGATTN_E_MASK: return "mask failed validation";
     case FGATTN_E_FLAGS: return "unknown flag bits";
+    case FGATTN_E_STATIC_LIMIT: return "fgattn_forward_static: more work items than FGATTN_STATIC_MAX_ITEMS";
     default: return "unknown fgattn error code";
   }
 }

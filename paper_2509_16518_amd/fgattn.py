@@ -21,7 +21,8 @@ class FgattnParams(ctypes.Structure):
 
 
 FLAG_STATIC_ASSIGN, FLAG_FIFO_QUEUE, FLAG_REUSE_PLAN, FLAG_MASK_ROWS_IN_HBM = 1, 2, 4, 8
-E_NULL, E_SHAPE, E_STRIDE, E_ALIGN, E_WORKSPACE, E_SCALE, E_DEVICE, E_MASK, E_FLAGS = range(-1, -10, -1)
+E_NULL, E_SHAPE, E_STRIDE, E_ALIGN, E_WORKSPACE, E_SCALE, E_DEVICE, E_MASK, E_FLAGS, E_STATIC_LIMIT = range(-1, -11, -1)
+STATIC_MAX_ITEMS = 65536
 
 _lib = None
 
@@ -45,6 +46,8 @@ def lib():
         L.fgattn_workspace_bytes.restype = ctypes.c_size_t
         L.fgattn_forward.argtypes = [vp, vp, vp, i64p, vp, pp, vp, vp, vp, ctypes.c_size_t, vp]
         L.fgattn_forward.restype = ctypes.c_int
+        L.fgattn_forward_static.argtypes = [vp, vp, vp, i64p, vp, pp, vp, vp, vp]
+        L.fgattn_forward_static.restype = ctypes.c_int
         L.fgattn_forward_part.argtypes = [vp, vp, vp, i64p, vp, pp, vp, vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
         L.fgattn_forward_part.restype = ctypes.c_int
         L.fgattn_forward_grouped.argtypes = [vp, vp, vp, vp, i64p, vp, vp, pp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -112,6 +115,13 @@ def fgattn_forward(q, k, v, mask_indptr, mask_indices, params, out, lse, workspa
                                 mask_indices.data_ptr(), ctypes.byref(params), out.data_ptr(), lse.data_ptr(),
                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                 _stream_ptr(stream)))
+
+
+def fgattn_forward_static(q, k, v, mask_indptr, mask_indices, params, out, lse, stream=None):
+    """The sparse forward pass without a workspace argument (scratch inside the library's device image)."""
+    _check(lib().fgattn_forward_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), mask_indptr.data_ptr(),
+                                       mask_indices.data_ptr(), ctypes.byref(params), out.data_ptr(), lse.data_ptr(),
+                                       _stream_ptr(stream)))
 
 
 PART_GATHER, PART_COMPUTE = 1, 2
