@@ -252,6 +252,23 @@ def main():
                         "gather_only_TBps": gather_bytes / ms_gather / 1e9,
                         "gather_TBps_in_full_kernel": gather_bytes / ms_main / 1e9,
                         "compute_only_pct_bf16_mfma_peak": 100.0 * useful / ms_compute / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+        if w.M == 64:
+            # how the gather half alone responds to more rows in flight and to fewer issuing waves: the fraction of
+            # the MFMA peak that the kernel could reach if everything else hid under its gathers
+            ms_ring3 = time_calls(part(F.PART_GATHER_RING3), 2, max(3, args.steps // 2))["mean"]
+            ms_one = time_calls(part(F.PART_GATHER_ONE_WG), 2, max(3, args.steps // 2))["mean"]
+            cus = torch.cuda.get_device_properties(0).multi_processor_count
+            clk = 2.4e9
+
+            def per_cu(ms):
+                return gather_bytes / (ms * 1e-3) / cus / clk
+            res["parts"].update({
+                "gather_only_k_ring_of_3_tiles_ms": ms_ring3, "gather_only_one_wg_per_cu_ms": ms_one,
+                "gather_bytes_per_clk_per_cu_at_2.4GHz": {"8_waves_2_tile_rings": per_cu(ms_gather),
+                                                          "8_waves_3_tile_k_ring": per_cu(ms_ring3),
+                                                          "4_waves_2_tile_rings": per_cu(ms_one)},
+                "frac_bf16_mfma_peak_if_gather_bound": {"2_tile_rings": useful / ms_gather / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                                                        "3_tile_k_ring": useful / ms_ring3 / 1e9 / MFMA_BF16_PEAK_TFLOPS}})
         del scratch_out, scratch_lse
     if args.mask and w.grid[0] * w.grid[1] * w.grid[2] == w.L and w.name == "wan-1.3b":
         # the step before the hot path (Sec. 4.3): top-p mask from block means, on Q/K with space-time locality

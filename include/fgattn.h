@@ -205,12 +205,16 @@ int fgattn_forward_static(const void* q, const void* k, const void* v, const int
 
 /* Runs one half of fgattn_forward's kernel on the same launch shape,
  * FGATTN_PART_GATHER = index translation and K/V row gathers only (the data movement of Sec. 4.1),
- * FGATTN_PART_COMPUTE = everything except the row gathers (MFMA, softmax, LDS reads on whatever the tiles hold).
- * Same arguments and error behaviour as fgattn_forward; only M = 64 or 128 with d = 128, N = 1 is built (else
- * FGATTN_E_SHAPE; an unknown `part` gives FGATTN_E_FLAGS).  `out` and `lse` are overwritten with meaningless
- * values. */
+ * FGATTN_PART_COMPUTE = everything except the row gathers (MFMA, softmax, LDS reads on whatever the tiles hold),
+ * FGATTN_PART_GATHER_RING3 = the gathers with a K ring of three tiles instead of two (more rows in flight),
+ * FGATTN_PART_GATHER_ONE_WG = the gathers with one workgroup per compute unit instead of two (half the issuing waves).
+ * Same arguments and error behaviour as fgattn_forward; only M = 64 or 128 with d = 128, N = 1 is built, the last
+ * two parts only M = 64 (else FGATTN_E_SHAPE; an unknown `part` gives FGATTN_E_FLAGS).  `out` and `lse` are
+ * overwritten with meaningless values. */
 #define FGATTN_PART_GATHER 1
 #define FGATTN_PART_COMPUTE 2
+#define FGATTN_PART_GATHER_RING3 3
+#define FGATTN_PART_GATHER_ONE_WG 4
 int fgattn_forward_part(const void* q, const void* k, const void* v, const int64_t* mask_indptr,
                         const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* workspace,
                         size_t workspace_bytes, int part, void* stream);

@@ -18,8 +18,8 @@ namespace fg {
 // built per head -- all workgroups drain one head before the next, so concurrently running
 // items share that head's K/V in cache -- and longest-first inside a head.
 // blockIdx.x = (batch, head) slice; blockIdx.y splits the slice's query blocks when they are ranked exactly.
-// workspace layout: int32 ctrl[64] (ctrl[0] queue head,
-// ctrl[1] finished-workgroup count), then int32 order[n_items].
+// workspace layout: int32 ctrl[64] (ctrl[1] finished-workgroup count, ctrl[8 + q] head of the
+// queue of XCD q, which covers the q-th eighth of the slices), then int32 order[n_items].
 // ------------------------------------------------------------------------------------------
 constexpr int kPlanThreads = 256;
 constexpr int kRankMax = 4096;     // slices with at most this many query blocks are ranked exactly
@@ -32,7 +32,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(const int64_t* indpt
   __shared__ int s_max;
   const int tid = threadIdx.x;
   const int64_t base = (int64_t)blockIdx.x * QB;
-  if (blockIdx.x == 0 && blockIdx.y == 0 && tid < 2) ctrl[tid] = 0;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && tid < 16) ctrl[tid] = 0;
   if (!sorted || indptr == nullptr) {
     if (blockIdx.y == 0)
       for (int j = tid; j < QB; j += kPlanThreads) order[base + j] = (int32_t)(base + j);
@@ -336,8 +336,9 @@ int fgattn_forward_part(const void* q, const void* k, const void* v, const int64
                         const int32_t* mask_indices, const fgattn_params* p, void* out, float* lse, void* workspace,
                         size_t workspace_bytes, int part, void* stream) {
   if (!mask_indptr || !mask_indices) return FGATTN_E_NULL;
-  if (part != FGATTN_PART_GATHER && part != FGATTN_PART_COMPUTE) return FGATTN_E_FLAGS;
+  if (part < FGATTN_PART_GATHER || part > FGATTN_PART_GATHER_ONE_WG) return FGATTN_E_FLAGS;
   if (p && ((p->M != 64 && p->M != 128) || p->d != 128 || p->N != 1)) return FGATTN_E_SHAPE;
+  if (p && p->M != 64 && part > FGATTN_PART_COMPUTE) return FGATTN_E_SHAPE;
   return fg::run_forward(q, k, v, mask_indptr, mask_indices, p, out, lse, workspace, workspace_bytes, stream, part);
 }
 

@@ -14,7 +14,7 @@ struct FwdArgs {
   const int64_t* indptr;   // null => dense: every key of [0, L) in order
   const int32_t* indices;
   const int32_t* order;    // work-item ids in processing order
-  int32_t* counter;        // queue head (zeroed by the pre-pass)
+  int32_t* counter;        // int32 ctrl[64]: [1] finished-workgroup count, [8 + q] head of the queue of XCD q (zeroed by the pre-pass)
   int64_t q_sb, q_sh, q_sl, k_sb, k_sh, k_sl, v_sb, v_sh, v_sl, o_sb, o_sh, o_sl;  // elements
   int32_t H, L, M, N, QB, n_items, static_assign;
   // group -> key expansion without divisions: NT = keys per LDS tile of the launched variant

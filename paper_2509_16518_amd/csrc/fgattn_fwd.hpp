@@ -10,9 +10,9 @@
 // "Efficient dense attention").  A gather instruction holds the wave that issues it until the
 // vector-memory path has taken it (~170 clocks under load); MFMAs issued before it keep
 // executing meanwhile, so each tile's key loop interleaves one gather with one MFMA of each
-// contraction, and keeps the softmax arithmetic in a separate vector-ALU phase.  Work items are
-// fetched from a device-side queue in the order a pre-pass wrote (Sec. 4.2 "Load balancing",
-// Appendix B).
+// contraction and a share of the previous tile's exponentials; the row max and the base decision
+// follow in a short vector-ALU phase.  Work items are fetched from per-XCD device-side queues in the
+// order a pre-pass wrote (Sec. 4.2 "Load balancing", Appendix B).
 //
 // Transposed formulation: scores are produced as S^T (keys x queries) so that, in the MFMA
 // accumulator layout, one lane owns one query column.  Row statistics (max, sum) are then
@@ -55,22 +55,7 @@ __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0
 // VGPR staging).  Written as inline assembly so that the compiler does not track the transfer:
 // the kernel orders these loads against LDS reads itself (vmcnt(0) + workgroup barrier once per
 // tile), which lets the gathers of later tiles stay in flight during all of a tile's matrix work.
-__device__ __forceinline__ void gather16_to_lds(const void* base, unsigned byte_off, unsigned lds_base) {
-  // base and lds_base are wave-uniform by construction; readfirstlane pins them to scalar registers
-  // (it folds away when the value already lives in one)
-  const uint64_t b64 = (uint64_t)(uintptr_t)base;
-  base = (const void*)(uintptr_t)(((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(b64 >> 32)) << 32) |
-                                  (unsigned)__builtin_amdgcn_readfirstlane((int)(b64 & 0xffffffffu)));
-  lds_base = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_base);
-  asm volatile(
-      "s_mov_b32 m0, %2 ; fg_m0\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %0, %1"
-      :
-      : "v"(byte_off), "s"(base), "s"(lds_base)
-      : "memory", "m0");
-}
-// The same transfer for a run of up to four 1 KiB loads that land back to back in LDS: M0 is written once
+// A run of up to four 1 KiB loads lands back to back in LDS: M0 is written once
 // (gather16_first) and the following loads (gather16_next<K>) add K KiB through the instruction offset.  That
 // offset also enters the global address, so `base_m4k` is the true base minus 4096 and the byte offset carries
 // +4096 - 1024*K (kept non-negative: the 32-bit offset is zero-extended).
@@ -119,7 +104,16 @@ __device__ __forceinline__ float lane_pair_sum(float x) {
 
 constexpr float kLazyLog2 = 8.0f;   // how far (log2 units) the exponent base may lag behind the running max
 
-template <int MT, int D>
+constexpr int cmin(int a, int b) { return a < b ? a : b; }
+constexpr int cgcd(int a, int b) { return b == 0 ? a : cgcd(b, a % b); }
+constexpr int clcm(int a, int b) { return a / cgcd(a, b) * b; }
+
+// Tiling and LDS ring of one workgroup.  KS / VS = slots of the K ring / V ring (tiles of NT keys): in iteration t the
+// workgroup reads K(t+1) and V(t-1) and gathers K(t+KS) and V(t+VS-2) into the slots that the previous iteration
+// released, so KS-1 K tiles and VS-1 V tiles can be in flight.  The forward pass is instantiated with two slots each
+// (deeper rings make the gather half alone faster -- a third K slot by 8% -- but not the whole kernel); the
+// measurement aid also builds the gather half with a K ring of three.
+template <int MT, int D, int KS = 2, int VS = 2>
 struct FwdCfg {
   static constexpr int RW = MT / 32;            // waves along query rows (32 rows each)
   static constexpr int KW = 4 / RW;             // waves along keys within a tile (32 keys each)
@@ -132,41 +126,53 @@ struct FwdCfg {
   static constexpr int SSTEPS = D / 16;         // MFMA steps along d for S^T
   static constexpr int DBLK = D / 32;           // 32-row blocks of O^T
   static constexpr int TENSOR_BYTES = NT * ROWB;
-  static constexpr int STAGE_BYTES = 2 * TENSOR_BYTES;
-  static constexpr int NSTAGE = 2;
-  static constexpr int BIAS_OFF = NSTAGE * STAGE_BYTES;
+  static constexpr int K_OFF = 0;
+  static constexpr int V_OFF = KS * TENSOR_BYTES;
+  static constexpr int RING_BYTES = (KS + VS) * TENSOR_BYTES;
+  static constexpr int BIAS_OFF = RING_BYTES;   // (variants with a per-key bias row only)
   static constexpr int MERGE_REGS = DBLK * 16 + 2;
   static constexpr int MERGE_BYTES = (KW - 1) * RW * MERGE_REGS * 256;
-  static constexpr int LDS_BYTES = BIAS_OFF + NSTAGE * NT * 4 + 16;
+  static constexpr int ITEM_OFF = RING_BYTES - 16;   // the work-item id is handed to the waves through the ring's last bytes
+  static constexpr int LDS_BYTES_BIAS = BIAS_OFF + 2 * NT * 4 + 16;
+  static constexpr int NKEYSETS = KS - VS + 3;  // key-row sets alive at once: tiles t+VS-2 (V gather) .. t+KS (K gather)
   static_assert(MT == 32 || MT == 64 || MT == 128, "query tile");
   static_assert(D == 64 || D == 128, "head dim");
-  static_assert(IPW >= 1 && RPW % RPI == 0 && RPW % 8 == 0, "loader shape");
-  static_assert(MERGE_BYTES <= NSTAGE * STAGE_BYTES, "merge scratch must fit in the tile buffers");
+  static_assert(KS >= 2 && VS >= 2 && KS >= VS, "ring depths");
+  static_assert(IPW >= 1 && RPW % RPI == 0 && (RPW & (RPW - 1)) == 0, "loader shape");
+  static_assert(MERGE_BYTES <= ITEM_OFF, "merge scratch must fit in the tile buffers, below the work-item word");
 };
 
 // Online softmax of one 32-key x 32-query score block held as an MFMA accumulator: one query per
 // lane (registers 8c..8c+7 of the accumulator are the keys 16c + 8*(e/4) + 4*(lane/32) + e%4).
 // First half: mask padded keys, new running max of this lane's query.
-// MEMBER >= 0 (grouped query tiles): the row holds, per key, the bit mask of the group members that selected it;
-// a query of member MEMBER keeps only the keys whose bit is set.
-template <bool MASKED>
+// MASK_ROW: a row in LDS says which keys to mask out -- bias 0 for a real key and -inf for a padded / out-of-range
+//   one, or, with member >= 0 (grouped query tiles), per key the bit mask of the group members that selected it (a
+//   query of member MEMBER keeps only the keys whose bit is set).
+// MASK_TAIL: only the tile's trailing positions are masked: accumulator row r of this lane is valid iff r < limit.
+enum { MASK_NONE = 0, MASK_ROW = 1, MASK_TAIL = 2 };
+template <int MASK>
 __device__ __forceinline__ void softmax_max(f32x16& S, const float* bias_keys, int g, float m_run, float& m_new,
-                                            int member = -1) {
-  if (MASKED && member >= 0) {
+                                            int member = -1, int limit = 0) {
+  if (MASK == MASK_ROW && member >= 0) {
 #pragma unroll
     for (int r4 = 0; r4 < 4; r4++) {
       i32x4 bv = *reinterpret_cast<const i32x4*>(bias_keys + 8 * r4 + 4 * g);
 #pragma unroll
       for (int e = 0; e < 4; e++) S[4 * r4 + e] = ((bv[e] >> member) & 1) ? S[4 * r4 + e] : -INFINITY;
     }
-  } else if (MASKED) {
-    // bias is 0 for a real key and -inf for a padded / out-of-range one
+  } else if (MASK == MASK_ROW) {
 #pragma unroll
     for (int r4 = 0; r4 < 4; r4++) {
       f32x4 bv = *reinterpret_cast<const f32x4*>(bias_keys + 8 * r4 + 4 * g);
 #pragma unroll
       for (int e = 0; e < 4; e++) S[4 * r4 + e] = bv[e] < 0.0f ? -INFINITY : S[4 * r4 + e];
     }
+  } else if (MASK == MASK_TAIL) {
+    // register 4*r4 + e holds key row 8*r4 + 4*g + e of the wave's 32 keys; `limit` already has the 4*g taken off
+#pragma unroll
+    for (int r4 = 0; r4 < 4; r4++)
+#pragma unroll
+      for (int e = 0; e < 4; e++) S[4 * r4 + e] = (8 * r4 + e) < limit ? S[4 * r4 + e] : -INFINITY;
   }
   float mx = fmaxf(S[0], S[1]);
 #pragma unroll
@@ -188,19 +194,69 @@ enum { NMODE_DENSE = 0, NMODE_N1 = 1, NMODE_GROUPS = 2, NMODE_GROUPS_SHORT = 3 }
 // the two halves of the kernel can be timed apart on the same launch shape).
 enum { PART_ALL = 0, PART_GATHER = 1, PART_COMPUTE = 2 };
 
+// Which variants keep a per-key row in LDS (bias / membership): a short last key group and grouped query tiles.
+// The others mask the ragged end of a list by position.
+constexpr bool variant_has_mask_row(int nmode, bool grouped) {
+  return grouped || nmode == NMODE_GROUPS_SHORT;
+}
+template <int MT, int D, int NMODE, bool GROUPED = false, int KS = 2, int VS = 2>
+constexpr int fwd_lds_bytes() {
+  using C = FwdCfg<MT, D, KS, VS>;
+  return variant_has_mask_row(NMODE, GROUPED) ? C::LDS_BYTES_BIAS : C::RING_BYTES;
+}
+
+// id loads of the variants without a mask row: plain per-lane loads written as inline assembly so that the compiler
+// does not track them.  (A tracked load makes the compiler wait with vmcnt(0) before the first use, which would also
+// wait for every gather in flight: the counter is shared and the compiler cannot see the gathers.)  The kernel waits
+// with the s_waitcnt that precedes each tile's barrier (wait_vmem_le(loaded) ties the register to that wait for the compiler);
+// consumers clamp what they read to [0, L), so even a register read too early could never address out of bounds.
+__device__ __forceinline__ void load_id_untracked(int& dst, const int32_t* src) {
+  asm volatile("global_load_dword %0, %1, off" : "=v"(dst) : "v"(src) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmem_le() {   // s_waitcnt vmcnt(N): at most N vector-memory loads still in flight
+  static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+template <int N>
+__device__ __forceinline__ void wait_vmem_le(int& loaded) {   // the same, and `loaded` (an untracked load's target) is valid after it
+  static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(loaded) : "n"(N) : "memory");
+}
+
 // GROUPED (paper Sec. 4.2): a work item is a GROUP of query tiles (a.tile_rows rows each, R = MT / tile_rows of
 // them, listed in a.group_tiles) that shares one gathered key list -- the union of the members' lists -- while
 // every member attends only to its own key blocks: a.memb holds, per entry of the union list, the bit mask of the
 // members that selected it, and scores of the others are set to -inf before the softmax.
-template <int MT, int D, int NMODE, int OCC, int PART = PART_ALL, bool GROUPED = false>
+template <int MT, int D, int NMODE, int OCC, int PART = PART_ALL, bool GROUPED = false, int KS = 2, int VS = 2>
 __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
-  using C = FwdCfg<MT, D>;
+  using C = FwdCfg<MT, D, KS, VS>;
   constexpr bool DENSE = NMODE == NMODE_DENSE;
   constexpr bool WAVE_PRIO = NMODE == NMODE_DENSE || NMODE == NMODE_N1;
+  constexpr bool MASK_ROWS = variant_has_mask_row(NMODE, GROUPED);   // per-key bias / membership row in LDS
+  constexpr bool ASM_IDS = NMODE == NMODE_N1 && !GROUPED;            // ids through untracked loads
+  // ... whose cross-lane permute is issued before the barrier that precedes its use (measured on one box: 2.4% faster
+  // at 128 query rows, 2.5% slower at 64, where a wave has twice the gathers to issue per tile and the extra wait for
+  // the ids at the end of an iteration delays the next one's)
+  constexpr bool EARLY_PERMUTE = ASM_IDS && MT == 128;
   static_assert(!GROUPED || (MT == 128 && (NMODE == NMODE_N1 || NMODE == NMODE_GROUPS_SHORT)),
                 "groups are 128 query rows with a sparse list (any L: the variant that masks positions past the end)");
+  static_assert(!MASK_ROWS || (KS == 2 && VS == 2), "the mask row is a two-slot ring and its id loads are tracked");
+  // vector-memory operations per iteration and wave, in program order: [ids (ASM_IDS)] [V gathers] [K gathers]
+  constexpr int PER = 2 * C::IPW + (ASM_IDS ? 1 : 0);
+  // What may still be in flight at the barrier that opens iteration t+1: everything issued after V(t) (gathered in
+  // iteration t+2-VS, first in its iteration) and after K(t+2) (gathered in iteration t+2-KS, last in its iteration)
+  constexpr int WAITN = cmin(C::IPW + (VS - 2) * PER, (KS - 2) * PER);
+  // ids are requested IDL iterations before they are turned into key rows; by then at least WAITN operations must
+  // have followed them (the smallest such lead, rounded up to a power of two to keep the unrolled loop short)
+  constexpr int IDL_MIN = ASM_IDS ? (WAITN <= 2 * C::IPW ? 1 : 1 + (WAITN - 2 * C::IPW + PER - 1) / PER) : 1;
+  constexpr int IDL = IDL_MIN <= 1 ? 1 : IDL_MIN <= 2 ? 2 : 4;
+  static_assert(IDL_MIN <= 4, "id lead");
+  constexpr int AFTER_IDS = 2 * C::IPW + (IDL - 1) * PER;   // operations issued after an id load by the end of the iteration before its use
+  static_assert(!ASM_IDS || (AFTER_IDS >= WAITN && AFTER_IDS <= 63), "id wait");
+  constexpr int U = clcm(clcm(KS, VS), clcm(2, IDL));   // iterations per unrolled loop body: every slot is an immediate
+  static_assert(U <= 12, "unroll");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  __shared__ int s_item;
 
   const int tid = threadIdx.x;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -214,7 +270,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
 
   float* bias = reinterpret_cast<float*>(smem + C::BIAS_OFF);
   // per bias-ring slot: tile number + 1 of the last tile that put a key to be masked out into the slot
-  int* masked_tile = reinterpret_cast<int*>(smem + C::BIAS_OFF + C::NSTAGE * C::NT * 4);
+  int* masked_tile = reinterpret_cast<int*>(smem + C::BIAS_OFF + 2 * C::NT * 4);
+  volatile int* s_item = reinterpret_cast<volatile int*>(smem + C::ITEM_OFF);
   const unsigned lds0 = lds_address(smem);
 
   // ---- LDS layout: rows of ROWB bytes, 16-byte chunks XOR-swizzled so that reads are bank-conflict free ----
@@ -253,20 +310,42 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
   // whole row)
   constexpr bool LAZY_BIAS = NMODE == NMODE_GROUPS_SHORT && !GROUPED;
   int iter = 0;
+  // the XCD this workgroup runs on (hardware register XCC_ID, bits 3:0) picks its home queue
+  const int my_xcd = __builtin_amdgcn_s_getreg((4 - 1) << 11 | 0 << 6 | 20) & 7;
+  int queues_left = 8;
   for (;;) {
     // ---------------- fetch the next work item ----------------
     if (a.static_assign) {
       int j = blockIdx.x + iter * gridDim.x;
-      if (tid == 0) s_item = j < a.n_items ? a.order[j] : -1;
+      if (tid == 0) *s_item = j < a.n_items ? a.order[j] : -1;
     } else {
+      // One queue per XCD (each XCD has its own L2): queue q holds the work of a contiguous eighth of the (batch, head)
+      // slices, in the order the pre-pass wrote, so that a head's K/V streams through one L2 instead of eight.  A
+      // workgroup drains the queue of the XCD it runs on, then moves on to the next ones and helps there; a queue once
+      // found empty stays empty, so `queues_left` only counts down.
       if (tid == 0) {
-        int j = atomicAdd(a.counter, 1);
-        s_item = j < a.n_items ? a.order[j] : -1;
+        int item = -1;
+        const int slices = a.n_items / a.QB;
+        while (queues_left > 0) {
+          const int q = (my_xcd + 8 - queues_left) & 7;
+          const int s0 = (q * slices) >> 3, s1 = ((q + 1) * slices) >> 3;
+          const int len = (s1 - s0) * a.QB;
+          if (len > 0) {
+            const int j = atomicAdd(a.counter + 8 + q, 1);
+            if (j < len) {
+              item = a.order[s0 * a.QB + j];
+              break;
+            }
+          }
+          queues_left--;
+        }
+        *s_item = item;
       }
     }
     iter++;
     __syncthreads();
-    const int w = __builtin_amdgcn_readfirstlane(s_item);
+    const int w = __builtin_amdgcn_readfirstlane(*s_item);
+    __syncthreads();   // the word lies inside the tile ring: every wave has read it before any gather may land there
     if (w < 0) break;
 
     const int slice = w / a.QB, qi = w - slice * a.QB;
@@ -318,22 +397,24 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     // ---------------- loader ----------------
     // Position p = T*NT + wv*RPW + i*RPI + lrow of the compacted list is fetched by this lane with load
     // instruction i of tile T.  Pipeline per tile T (one iteration per tile, one barrier each):
-    //   iteration T-3: group ids fetched          iteration T-2: ids -> key rows, K(T) gathered
-    //   iteration T-1: S(T) = K(T) Q^T, row max   iteration T  : V(T) gathered; P(T) = exp(S(T) - m)
-    //   iteration T+1: O += V(T)^T P(T)^T
+    //   iteration T-KS-IDL: group ids requested     iteration T-KS : ids -> key rows, K(T) gathered
+    //   iteration T-1     : S(T) = K(T) Q^T, row max iteration T-VS+2: V(T) gathered
+    //   iteration T       : P(T) = exp(S(T) - m)     iteration T+1  : O += V(T)^T P(T)^T
     // Past the end of the list the pipeline keeps running on the last tile again (clamped tile index): a few
     // redundant, in-bounds gathers per work item instead of existence checks in every iteration.
     int gi[C::IPW];       // group ids being fetched (next tile to convert)
     int gm[C::IPW];       // GROUPED: their membership masks
     int wi[C::IPW];       // offset of the key inside its group (NMODE_GROUPS)
-    int widx = 0;         // coalesced id fetch: lane j holds the id of row j % RPW of this wave's rows
-    int keyA[C::IPW], keyB[C::IPW], keyC[C::IPW];   // key rows of tiles t, t+1, t+2 in iteration t
+    int widx[IDL];        // coalesced id fetch: lane j holds the id of row j % RPW of this wave's rows; tile T in widx[T % IDL]
+    // key rows of tiles t+VS-2 .. t+KS in iteration t (set 0 feeds the V gathers, the last set the K gathers)
+    int keys[C::NKEYSETS][C::IPW];
+    constexpr int KNEW = C::NKEYSETS - 1;
     int tq = 0, tr = 0;   // (T*NT) / N and (T*NT) % N for the next tile to fetch ids for, advanced without divisions
     const int lpos = wv * C::RPW + lrow;
     const int last = ntiles - 1;
     const uint8_t* memb = GROUPED ? a.memb + beg : nullptr;
-    // a tile whose positions need a per-key entry in the bias row: short last group, ragged last tile, or (GROUPED)
-    // always, since the row then carries the membership masks
+    // a tile whose positions need checking: short last group, ragged last tile, or (GROUPED) always, since the mask
+    // row then carries the membership masks
     auto tile_needs_check = [&](int T) { return GROUPED || short_group || (T + 1) * C::NT > total; };
     // ... and whether the scores of tile T need the bias row at all: with a short last group only the tiles that
     // contain it do, and the lanes that loaded its missing keys have said so in masked_tile (a stale entry of an
@@ -346,11 +427,16 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     };
     // full tiles with one key per group: one coalesced load per wave brings the RPW ids of its rows;
     // a cross-lane permute then hands each lane the id of its own row
-    auto coalesced_ids = [&](int T) { return NMODE == NMODE_N1 && !tile_needs_check(T); };
-    auto fetch_ids = [&](int T) {
+    auto coalesced_ids = [&](int T) { return NMODE == NMODE_N1 && (ASM_IDS || !tile_needs_check(T)); };
+    auto fetch_ids = [&](int T, int& wdst) {
       if (NMODE == NMODE_DENSE) return;
+      if constexpr (ASM_IDS) {
+        // (the position is clamped into the list: a ragged last tile masks what lies past the end by position)
+        load_id_untracked(wdst, idx + min(T * C::NT + wv * C::RPW + (lane & (C::RPW - 1)), cnt - 1));
+        return;
+      }
       if (__builtin_expect(coalesced_ids(T), 1)) {
-        widx = idx[T * C::NT + wv * C::RPW + (lane & (C::RPW - 1))];
+        wdst = idx[T * C::NT + wv * C::RPW + (lane & (C::RPW - 1))];
         return;
       }
 #pragma unroll
@@ -377,12 +463,40 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         }
       }
     };
-    // ids of tile T (fetched earlier) -> key rows in keyC; padded / out-of-range positions of a checked tile
-    // read the item's first active row and get a -inf score bias
-    auto make_keys = [&](int T) {
+    // Variants without a mask row turn ids into key rows in two steps, so that the cross-lane permute of the first has
+    // the gather phase's first slots to complete before the second consumes it:
+    //   keys_begin: ids of tile T (in wsrc) -> this lane's raw ids (one key per group: a permute is issued, nothing waits);
+    //   keys_finish: raw ids -> key rows, clamped into the K/V slice; positions past the end of the list read the
+    //   item's first active row (their scores are masked out by position).
+    auto keys_begin = [&](int T, int wsrc, int (&kdst)[C::IPW]) {
+#pragma unroll
+      for (int i = 0; i < C::IPW; i++) {
+        if constexpr (DENSE) kdst[i] = T * C::NT + lpos + i * C::RPI;
+        else if constexpr (NMODE == NMODE_N1) kdst[i] = __builtin_amdgcn_ds_bpermute((i * C::RPI + lrow) << 2, wsrc);
+        else kdst[i] = (int)__umul24((unsigned)gi[i], (unsigned)N) + wi[i];   // (group id and N are below 2^24, and so is their product)
+      }
+    };
+    auto keys_finish = [&](int T, int (&kdst)[C::IPW]) {
+      if constexpr (!DENSE) {   // clamped: whatever the register held, the gather stays inside the K/V slice
+#pragma unroll
+        for (int i = 0; i < C::IPW; i++) kdst[i] = (int)min((unsigned)kdst[i], (unsigned)(a.L - 1));
+      }
+      if (__builtin_expect(tile_needs_check(T), 0)) {
+#pragma unroll
+        for (int i = 0; i < C::IPW; i++) kdst[i] = T * C::NT + lpos + i * C::RPI < total ? kdst[i] : pad_key;
+      }
+    };
+    // ids of tile T (fetched earlier, in wsrc) -> key rows in kdst; padded / out-of-range positions of a checked tile
+    // read the item's first active row and have their scores masked out
+    auto make_keys = [&](int T, int wsrc, int (&kdst)[C::IPW]) {
+      if constexpr (!MASK_ROWS) {
+        keys_begin(T, wsrc, kdst);
+        keys_finish(T, kdst);
+        return;
+      }
       if (NMODE == NMODE_N1 && __builtin_expect(coalesced_ids(T), 1)) {
 #pragma unroll
-        for (int i = 0; i < C::IPW; i++) keyC[i] = __builtin_amdgcn_ds_bpermute((i * C::RPI + lrow) << 2, widx);
+        for (int i = 0; i < C::IPW; i++) kdst[i] = __builtin_amdgcn_ds_bpermute((i * C::RPI + lrow) << 2, wsrc);
         return;
       }
       const bool checked = tile_needs_check(T);
@@ -392,7 +506,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         for (int i = 0; i < C::IPW; i++) {
           const int p = T * C::NT + lpos + i * C::RPI;
           // (group id and N are below 2^24 and so is their product, a key row)
-          int key = NMODE == NMODE_DENSE ? p : NMODE == NMODE_N1 ? gi[i] : (int)__umul24((unsigned)gi[i], (unsigned)N) + wi[i];
+          int key = NMODE == NMODE_N1 ? gi[i] : (int)__umul24((unsigned)gi[i], (unsigned)N) + wi[i];
           if (__builtin_expect(checked, 0)) {
             const bool ok = p < total && key < a.L;
             key = ok ? key : pad_key;
@@ -403,7 +517,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
                 bias[(T & 1) * C::NT + lpos + i * C::RPI] = ok ? 0.0f : -INFINITY;
             }
           }
-          keyC[i] = key;
+          kdst[i] = key;
         }
         return;
       }
@@ -420,7 +534,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         int key = (int)__umul24((unsigned)gi[i], (unsigned)N) + wi[i];
         ok[i] = !checked || (p < total && key < a.L);
         any_bad |= !ok[i];
-        keyC[i] = ok[i] ? key : pad_key;
+        kdst[i] = ok[i] ? key : pad_key;
       }
       if (__builtin_expect(rewrite || __builtin_amdgcn_ballot_w64(any_bad) != 0, 0)) {
         if (pc == 0) {
@@ -432,8 +546,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         slot_dirty[T & 1] = false;   // (a row left alone by unchecked tiles stays dirty until a tile rewrites it)
       }
     };
-    // LDS: K ring slots 0,1 then V ring slots 0,1, TENSOR_BYTES each.  A run of up to four gathers of one wave
-    // lands back to back, so only the first writes M0 and the others use the instruction offset (which also
+    // LDS: K ring slots 0..KS-1 then V ring slots 0..VS-1, TENSOR_BYTES each.  A run of up to four gathers of one
+    // wave lands back to back, so only the first writes M0 and the others use the instruction offset (which also
     // enters the global address: base - 4096 and a per-lane constant + 4096 - 1024*(i%4) compensate).
     unsigned kcon[C::IPW], vcon[C::IPW];
 #pragma unroll
@@ -446,23 +560,42 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     }
     const char* kbase_m4k = reinterpret_cast<const char*>(kbase) - 4096;
     const char* vbase_m4k = reinterpret_cast<const char*>(vbase) - 4096;
-    auto gather_k = [&](auto ic, int slot, const int (&keys)[C::IPW]) {
+    auto gather_k = [&](auto ic, int slot, const int (&kk)[C::IPW]) {
       constexpr int i = decltype(ic)::value;
       if constexpr (PART == PART_COMPUTE) return;
-      const unsigned off = __umul24((unsigned)keys[i], k_rowb) + kcon[i];
+      const unsigned off = __umul24((unsigned)kk[i], k_rowb) + kcon[i];
       if constexpr ((i & 3) == 0)
-        gather16_first(kbase_m4k, off, lds0 + slot * C::TENSOR_BYTES + (wv * C::RPW + i * C::RPI) * C::ROWB);
+        gather16_first(kbase_m4k, off, lds0 + C::K_OFF + slot * C::TENSOR_BYTES + (wv * C::RPW + i * C::RPI) * C::ROWB);
       else
         gather16_next<(i & 3)>(kbase_m4k, off);
     };
-    auto gather_v = [&](auto ic, int slot, const int (&keys)[C::IPW]) {
+    auto gather_v = [&](auto ic, int slot, const int (&kk)[C::IPW]) {
       constexpr int i = decltype(ic)::value;
       if constexpr (PART == PART_COMPUTE) return;
-      const unsigned off = __umul24((unsigned)keys[i], v_rowb) + vcon[i];
+      const unsigned off = __umul24((unsigned)kk[i], v_rowb) + vcon[i];
       if constexpr ((i & 3) == 0)
-        gather16_first(vbase_m4k, off, lds0 + (2 + slot) * C::TENSOR_BYTES + (wv * C::RPW + i * C::RPI) * C::ROWB);
+        gather16_first(vbase_m4k, off, lds0 + C::V_OFF + slot * C::TENSOR_BYTES + (wv * C::RPW + i * C::RPI) * C::ROWB);
       else
         gather16_next<(i & 3)>(vbase_m4k, off);
+    };
+    // all of one tile's K (or V) gathers of this wave, back to back (prologue)
+    auto burst_k = [&](int slot, const int (&kk)[C::IPW]) {
+      gather_k(std::integral_constant<int, 0>(), slot, kk);
+      if constexpr (C::IPW > 1) gather_k(std::integral_constant<int, 1>(), slot, kk);
+      if constexpr (C::IPW > 2) { gather_k(std::integral_constant<int, 2>(), slot, kk); gather_k(std::integral_constant<int, 3>(), slot, kk); }
+      if constexpr (C::IPW > 4) {
+        gather_k(std::integral_constant<int, 4>(), slot, kk); gather_k(std::integral_constant<int, 5>(), slot, kk);
+        gather_k(std::integral_constant<int, 6>(), slot, kk); gather_k(std::integral_constant<int, 7>(), slot, kk);
+      }
+    };
+    auto burst_v = [&](int slot, const int (&kk)[C::IPW]) {
+      gather_v(std::integral_constant<int, 0>(), slot, kk);
+      if constexpr (C::IPW > 1) gather_v(std::integral_constant<int, 1>(), slot, kk);
+      if constexpr (C::IPW > 2) { gather_v(std::integral_constant<int, 2>(), slot, kk); gather_v(std::integral_constant<int, 3>(), slot, kk); }
+      if constexpr (C::IPW > 4) {
+        gather_v(std::integral_constant<int, 4>(), slot, kk); gather_v(std::integral_constant<int, 5>(), slot, kk);
+        gather_v(std::integral_constant<int, 6>(), slot, kk); gather_v(std::integral_constant<int, 7>(), slot, kk);
+      }
     };
 
     // ---------------- accumulators ----------------
@@ -492,16 +625,24 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
       s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS s16x4*)(p0 + 8 * C::ROWB));
       return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // Phase X.  O^T += V^T P^T with V in slot `vslot` (a constant) and, with QK, Sn = K Q^T with K in the same
-    // slot number of the K ring: one MFMA of each per slot.  With GATHER, every slot also issues one of this
-    // iteration's gathers: V rows of the current tile (keys in keyA) -> the V slot this phase does not read, then
-    // K rows of the tile after next (keys in keyC) -> the K slot this phase does not read.  The gather holds the
-    // wave; the two MFMAs just issued execute underneath it.
-    auto x_phase = [&](auto vslot, const i32x4 (&Pin)[2], auto with_gather, auto with_qk, f32x16& Sn) {
+    // Phase X.  O^T += V^T P^T with V in slot `vrd` of the V ring and, with QK, Sn = K Q^T with K in slot `krd` of the K
+    // ring: one MFMA of each per slot.  With EXP, every slot also takes its share of the exponentials of the previous
+    // tile's scores So: P = exp2(c*(So - m)) packed to bf16 into Pout, and the row sum; they issue while the two matrix
+    // instructions just issued execute.  With GATHER, every slot then issues one of this iteration's gathers: V rows
+    // (keys in key set 0) -> V slot `vwr`, then K rows (keys in the newest key set) -> K slot `kwr`, both released by
+    // the previous iteration.  The gather holds the wave; the matrix instructions execute underneath it.
+    auto x_phase = [&](auto vrd_c, auto krd_c, auto vwr_c, auto kwr_c, const i32x4 (&Pin)[2], auto with_gather,
+                       auto with_qk, f32x16& Sn, auto with_exp, const f32x16& So, i32x4 (&Pout)[2]) {
+      constexpr int vrd = decltype(vrd_c)::value, krd = decltype(krd_c)::value;
+      constexpr int vwr = decltype(vwr_c)::value, kwr = decltype(kwr_c)::value;
       constexpr bool GATHER = decltype(with_gather)::value;
-      constexpr bool QK = decltype(with_qk)::value && PART != PART_GATHER;   // also Sn = K(slot vslot) Q^T
-      const unsigned char* vst = smem + (2 + vslot) * C::TENSOR_BYTES;
-      const unsigned char* kst = smem + vslot * C::TENSOR_BYTES;
+      constexpr bool QK = decltype(with_qk)::value && PART != PART_GATHER;   // also Sn = K(slot krd) Q^T
+      constexpr bool EXP = decltype(with_exp)::value && PART != PART_GATHER;  // also P = exp2(c*(So - m)) -> Pout, row sum
+      const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;   // a wave that has seen no valid key yet
+      const float neg_mc = -m_safe * a.c_log2;
+      float psum0 = 0.0f, psum1 = 0.0f;
+      const unsigned char* vst = smem + C::V_OFF + vrd * C::TENSOR_BYTES;
+      const unsigned char* kst = smem + C::K_OFF + krd * C::TENSOR_BYTES;
       auto read_kf = [&](int s) {
         return __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kst + (kor ^ (32 * s))));
       };
@@ -527,15 +668,31 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
           if constexpr (e + AHEAD < NE) kf[e + AHEAD] = read_kf(e + AHEAD);
           Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[e], qf[e], Sn, 0, 0, 0);
         }
+        if constexpr (EXP) {
+#pragma unroll
+          for (int x = 0; x < VPS; x += 2) {
+            const int r = e * VPS + x;
+            // masked keys hold S = -inf and c_log2 > 0 (the host substitutes a tiny positive value for
+            // scale = 0), so their p is exactly 0 without a select
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(So[r], a.c_log2, neg_mc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(So[r + 1], a.c_log2, neg_mc));
+            psum0 += p0;
+            psum1 += p1;
+            f32x2 pp = {p0, p1};
+            int pk = __builtin_bit_cast(int, __builtin_convertvector(pp, bf16x2));
+            asm volatile("" : "+v"(pk));   // keeps the compiler from sinking the conversion out of the slot
+            Pout[r >> 3][(r & 7) >> 1] = pk;
+          }
+        }
         if constexpr (GATHER) {
           if constexpr (e % DMA_EVERY == 0) {
             constexpr int j0 = (e / DMA_EVERY) * DMA_PER;
-            if constexpr (j0 < C::IPW) gather_v(std::integral_constant<int, j0>(), 1 - vslot, keyA);
-            else if constexpr (j0 < NDMA) gather_k(std::integral_constant<int, j0 - C::IPW>(), 1 - vslot, keyC);
+            if constexpr (j0 < C::IPW) gather_v(std::integral_constant<int, j0>(), vwr, keys[0]);
+            else if constexpr (j0 < NDMA) gather_k(std::integral_constant<int, j0 - C::IPW>(), kwr, keys[KNEW]);
             if constexpr (DMA_PER > 1) {
               constexpr int j1 = j0 + 1;
-              if constexpr (j1 < C::IPW) gather_v(std::integral_constant<int, j1>(), 1 - vslot, keyA);
-              else if constexpr (j1 < NDMA) gather_k(std::integral_constant<int, j1 - C::IPW>(), 1 - vslot, keyC);
+              if constexpr (j1 < C::IPW) gather_v(std::integral_constant<int, j1>(), vwr, keys[0]);
+              else if constexpr (j1 < NDMA) gather_k(std::integral_constant<int, j1 - C::IPW>(), kwr, keys[KNEW]);
             }
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -551,105 +708,74 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         slot(std::integral_constant<int, 6>());
         slot(std::integral_constant<int, 7>());
       }
+      if (EXP) l_run += psum0 + psum1;
     };
-    // Phase Y, vector ALU only in the key loop.  With EXP: P = exp2(c*(So - m)) of the previous tile's scores So,
-    // row sum, bf16 pack into Pout.  Then the row max of the new scores Sn (tile Tm) and the rare decision to
-    // move the exponent base (see kLazyLog2).  Also rotates the key-row sets (t+1 -> t, t+2 -> t+1).  With MFMA
-    // (prologue only) it first computes Sn = K Q^T with K in slot `kslot`.
-    auto y_phase = [&](auto kslot, int Tm, f32x16& Sn, const f32x16& So, i32x4 (&Pout)[2], auto with_exp,
-                        auto with_mfma) {
-      constexpr bool EXP = decltype(with_exp)::value;
+    // Phase Y, vector ALU only in the key loop: the row max of the new scores Sn (tile Tm) and the rare decision to
+    // move the exponent base (see kLazyLog2).  With MFMA (prologue only) it first computes Sn = K Q^T with K in slot
+    // `kslot` of the K ring.
+    auto y_phase = [&](auto kslot, int Tm, f32x16& Sn, auto with_mfma) {
       constexpr bool MFMA = decltype(with_mfma)::value;
       // written before the barrier that precedes this phase; consumed at its end
       const int masked_entry = LAZY_BIAS ? masked_tile[Tm & 1] : 0;
-      if constexpr (PART == PART_GATHER) {   // only the bookkeeping the gathers depend on
-#pragma unroll
-        for (int i = 0; i < C::IPW; i++) {
-          keyA[i] = keyB[i];
-          keyB[i] = keyC[i];
-        }
-        return;
-      }
-      const unsigned char* kst = smem + kslot * C::TENSOR_BYTES;
-      auto read_kf = [&](int s) {
-        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kst + (kor ^ (32 * s))));
-      };
-      const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;   // a wave that has seen no valid key yet
-      const float neg_mc = -m_safe * a.c_log2;
-      float psum0 = 0.0f, psum1 = 0.0f;
-      bf16x8 kf[NE];
+      if constexpr (PART == PART_GATHER) return;
       if constexpr (MFMA) {
+        const unsigned char* kst = smem + C::K_OFF + kslot * C::TENSOR_BYTES;
+        auto read_kf = [&](int s) {
+          return __builtin_bit_cast(bf16x8, *reinterpret_cast<const i32x4*>(kst + (kor ^ (32 * s))));
+        };
+        bf16x8 kf[NE];
 #pragma unroll
         for (int e = 0; e < AHEAD; e++) kf[e] = read_kf(e);
 #pragma unroll
         for (int r = 0; r < 16; r++) Sn[r] = 0.0f;
-      }
-      auto slot = [&](auto ec) {
-        constexpr int e = decltype(ec)::value;
-        if constexpr (MFMA) {
-          if constexpr (e + AHEAD < NE) kf[e + AHEAD] = read_kf(e + AHEAD);
+#pragma unroll
+        for (int e = 0; e < NE; e++) {
+          if (e + AHEAD < NE) kf[e + AHEAD] = read_kf(e + AHEAD);
           Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[e], qf[e], Sn, 0, 0, 0);
         }
-        if constexpr (EXP) {
-#pragma unroll
-          for (int x = 0; x < VPS; x += 2) {
-            const int r = e * VPS + x;
-            // masked keys hold S = -inf and c_log2 > 0 (the host substitutes a tiny positive value for
-            // scale = 0), so their p is exactly 0 without a select
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(So[r], a.c_log2, neg_mc));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(So[r + 1], a.c_log2, neg_mc));
-            psum0 += p0;
-            psum1 += p1;
-            f32x2 pp = {p0, p1};
-            int pk = __builtin_bit_cast(int, __builtin_convertvector(pp, bf16x2));
-            // the packed pair is consumed only after the next barrier; the pin keeps the compiler from sinking the
-            // exponentials there, into the phase whose issue slots belong to the gathers
-            asm volatile("" : "+v"(pk));
-            Pout[r >> 3][(r & 7) >> 1] = pk;
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      };
-      slot(std::integral_constant<int, 0>());
-      slot(std::integral_constant<int, 1>());
-      slot(std::integral_constant<int, 2>());
-      slot(std::integral_constant<int, 3>());
-      if constexpr (NE > 4) {
-        slot(std::integral_constant<int, 4>());
-        slot(std::integral_constant<int, 5>());
-        slot(std::integral_constant<int, 6>());
-        slot(std::integral_constant<int, 7>());
-      }
-      if (EXP) l_run += psum0 + psum1;
-#pragma unroll
-      for (int i = 0; i < C::IPW; i++) {
-        keyA[i] = keyB[i];
-        keyB[i] = keyC[i];
       }
       float m_new;
       // (the same in every wave of the workgroup)
       const bool masked = LAZY_BIAS ? tile_has_masked_keys(Tm, masked_entry) : tile_needs_check(Tm);
-      if (__builtin_expect(masked, 0))
-        softmax_max<true>(Sn, bias + (Tm & 1) * C::NT + kw * 32, g, m_pend, m_new, GROUPED ? my_member : -1);
-      else
-        softmax_max<false>(Sn, nullptr, g, m_pend, m_new);
+      if (__builtin_expect(masked, 0)) {
+        if constexpr (MASK_ROWS)
+          softmax_max<MASK_ROW>(Sn, bias + (Tm & 1) * C::NT + kw * 32, g, m_pend, m_new, GROUPED ? my_member : -1);
+        else   // positions of the tile at and past `total` are padding
+          softmax_max<MASK_TAIL>(Sn, nullptr, g, m_pend, m_new, -1, total - Tm * C::NT - kw * 32 - 4 * g);
+      } else {
+        softmax_max<MASK_NONE>(Sn, nullptr, g, m_pend, m_new);
+      }
       if constexpr (LAZY_BIAS) slot_dirty[Tm & 1] |= masked;
       m_pend = m_new;
       const bool lane_moves = (m_run == -INFINITY) ? (m_new > m_run) : ((m_new - m_run) * a.c_log2 > kLazyLog2);
       resc = __builtin_amdgcn_ballot_w64(lane_moves) != 0;
     };
+    auto rotate_keys = [&]() {
+#pragma unroll
+      for (int s = 0; s + 1 < C::NKEYSETS; s++)
+#pragma unroll
+        for (int i = 0; i < C::IPW; i++) keys[s][i] = keys[s + 1][i];
+    };
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
-    // Iteration t, PAR = t & 1 (a constant, so every LDS slot is an immediate):
-    //   X: O += V(t-1)^T P(t-1)^T (V slot PAR^1)  ||  S(t+1) = K(t+1) Q^T (K slot PAR^1)  ||  gathers V(t) -> V slot
-    //      PAR and K(t+2) -> K slot PAR
-    //   Y: P(t) = exp(S(t) - m) and the row max of S(t+1), on the vector ALU
-    // Every gathered tile thus has phase Y and the barrier's wait to arrive before it is published.
-    auto iteration = [&](int t, auto parc, const i32x4 (&Pin)[2], i32x4 (&Pout)[2], f32x16& Sn, const f32x16& So) {
-      constexpr int PAR = decltype(parc)::value;
-      // K(t+1) and V(t-1), gathered during the previous iteration, become visible to every wave; every wave is
-      // done reading K(t) and V(t-2), whose slots this iteration refills
-      wait_vmem_all();
+    // Iteration t, J = t mod U (a constant, so every LDS slot and register set is an immediate):
+    //   X: O += V(t-1)^T P(t-1)^T  ||  S(t+1) = K(t+1) Q^T  ||  P(t) = exp(S(t) - m)  ||  gathers V(t+VS-2) and K(t+KS)
+    //      into the slots that iteration t-1 read last
+    //   Y: the row max of S(t+1), on the vector ALU
+    // A gathered tile has at least phase Y and the barrier's wait to arrive before it is published, and whole
+    // iterations more where the rings are deeper than two tiles.
+    auto iteration = [&](auto jc, int t) {
+      constexpr int J = decltype(jc)::value;
+      constexpr int PAR = J & 1;
+      i32x4 (&Pin)[2] = PAR ? PA : PB;
+      i32x4 (&Pout)[2] = PAR ? PB : PA;
+      f32x16& Sn = PAR ? SA : SB;
+      const f32x16& So = PAR ? SB : SA;
+      // K(t+1) and V(t-1) become visible to every wave: all but the WAITN most recent vector-memory operations of this
+      // wave have completed (they complete in order), which covers its share of both tiles and the ids converted
+      // below; every wave is done reading K(t) and V(t-2), whose slots this iteration refills
+      if constexpr (ASM_IDS) wait_vmem_le<WAITN>(widx[(J + KS) % IDL]);
+      else wait_vmem_le<WAITN>();
       __syncthreads();
       float alpha = 1.0f;
       if (__builtin_expect(resc, 0)) {   // the exponent base moves: l now, O after the MFMAs of the old base
@@ -657,14 +783,19 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         l_run *= alpha;
         m_run = m_pend;
       }
-      make_keys(min(t + 2, last));        // ids fetched during the previous iteration -> keyC
-      fetch_ids(min(t + 3, last));
+      // ids requested IDL iterations ago -> key rows (with untracked id loads the cross-lane permute was already
+      // issued before the barrier, at the end of the previous iteration, and only its result is consumed here)
+      if constexpr (EARLY_PERMUTE) keys_finish(min(t + KS, last), keys[KNEW]);
+      else make_keys(min(t + KS, last), widx[(J + KS) % IDL], keys[KNEW]);
+      fetch_ids(min(t + KS + IDL, last), widx[(J + KS) % IDL]);
       // wave priority: the gather phase above the vector-ALU phase above everything outside the key loop, so that
       // the waves that feed the memory pipe are issued first and a neighbour's prologue or epilogue never delays them
       // (measured: 1-3% faster with one key per group, 6% for the dense kernel at 128 rows; slower with N keys per
       // group, whose loaders do more vector-ALU work, so not used there)
       if constexpr (WAVE_PRIO) __builtin_amdgcn_s_setprio(3);
-      x_phase(std::integral_constant<int, PAR ^ 1>(), Pin, yes(), yes(), Sn);
+      x_phase(std::integral_constant<int, (J + U - 1) % VS>(), std::integral_constant<int, (J + 1) % KS>(),
+              std::integral_constant<int, (J + U - 2) % VS>(), std::integral_constant<int, J % KS>(), Pin, yes(), yes(), Sn,
+              yes(), So, Pout);
       if constexpr (WAVE_PRIO) __builtin_amdgcn_s_setprio(1);
       if (__builtin_expect(resc, 0)) {
 #pragma unroll
@@ -672,69 +803,89 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
 #pragma unroll
           for (int r = 0; r < 16; r++) O[db][r] *= alpha;
       }
-      y_phase(std::integral_constant<int, PAR ^ 1>(), min(t + 1, last), Sn, So, Pout, yes(), no());
+      y_phase(std::integral_constant<int, 0>(), min(t + 1, last), Sn, no());
+      rotate_keys();
+      if constexpr (EARLY_PERMUTE) {
+        // the ids of the tile whose K rows the next iteration gathers have arrived (their load was followed by
+        // AFTER_IDS operations): hand them to the lanes now, so that the permute's latency passes in the barrier
+        wait_vmem_le<AFTER_IDS>(widx[(J + 1 + KS) % IDL]);
+        keys_begin(min(t + 1 + KS, last), widx[(J + 1 + KS) % IDL], keys[KNEW]);
+      }
     };
 
     if (ntiles > 0) {
-      // prologue: K(0) -> K slot 0; V(0) -> V slot 1, only so that the first iteration's O += V^T P^T (with
-      // P = 0) multiplies finite numbers; then S(0) = K(0) Q^T while K(1) loads
+      // prologue: K(0) .. K(KS-1) -> their K slots; V(0) .. V(VS-3) -> their V slots; V(0) also -> the V slot that the
+      // first iteration reads as "V(-1)", only so that its O += V^T P^T (with P = 0) multiplies finite numbers; then
+      // S(0) = K(0) Q^T
 #pragma unroll
       for (int c = 0; c < 2; c++)
 #pragma unroll
         for (int e = 0; e < 4; e++) PB[c][e] = 0;
-      fetch_ids(0);
-      make_keys(0);
+      int wpro[KS];   // ids of tiles 0 .. KS-1 (ASM_IDS: requested together)
+      if constexpr (ASM_IDS) {
 #pragma unroll
-      for (int i = 0; i < C::IPW; i++) keyA[i] = keyB[i] = keyC[i];
-      auto burst = [&](auto ic) {
-        gather_k(ic, 0, keyC);
-      };
-      auto burst_v = [&](auto ic) {
-        gather_v(ic, 1, keyC);
-      };
-      burst(std::integral_constant<int, 0>());
-      if constexpr (C::IPW > 1) burst(std::integral_constant<int, 1>());
-      if constexpr (C::IPW > 2) { burst(std::integral_constant<int, 2>()); burst(std::integral_constant<int, 3>()); }
-      if constexpr (C::IPW > 4) {
-        burst(std::integral_constant<int, 4>()); burst(std::integral_constant<int, 5>());
-        burst(std::integral_constant<int, 6>()); burst(std::integral_constant<int, 7>());
+        for (int T = 0; T < KS; T++) fetch_ids(min(T, last), wpro[T]);
+#pragma unroll
+        for (int T = 0; T < IDL; T++) fetch_ids(min(KS + T, last), widx[(KS + T) % IDL]);
+#pragma unroll
+        for (int T = 0; T < KS; T++) wait_vmem_le<0>(wpro[T]);
       }
-      burst_v(std::integral_constant<int, 0>());
-      if constexpr (C::IPW > 1) burst_v(std::integral_constant<int, 1>());
-      if constexpr (C::IPW > 2) { burst_v(std::integral_constant<int, 2>()); burst_v(std::integral_constant<int, 3>()); }
-      if constexpr (C::IPW > 4) {
-        burst_v(std::integral_constant<int, 4>()); burst_v(std::integral_constant<int, 5>());
-        burst_v(std::integral_constant<int, 6>()); burst_v(std::integral_constant<int, 7>());
+      int ktmp[C::IPW];
+#pragma unroll
+      for (int T = 0; T < KS; T++) {
+        if constexpr (!ASM_IDS) fetch_ids(min(T, last), wpro[T]);
+        make_keys(min(T, last), wpro[T], ktmp);
+        burst_k(T, ktmp);
+        if (T == 0) {
+          burst_v(VS - 1, ktmp);
+#pragma unroll
+          for (int s = 0; s < C::NKEYSETS; s++)
+#pragma unroll
+            for (int i = 0; i < C::IPW; i++) keys[s][i] = ktmp[i];
+        }
+        if (T <= VS - 3) burst_v(T, ktmp);
+        if (T >= VS - 2) {
+#pragma unroll
+          for (int i = 0; i < C::IPW; i++) keys[T - (VS - 2)][i] = ktmp[i];
+        }
       }
-      fetch_ids(min(1, last));
-      wait_vmem_all();      // ids of tile 1
-      make_keys(min(1, last));
-      auto burst1 = [&](auto ic) { gather_k(ic, 1, keyC); };
-      burst1(std::integral_constant<int, 0>());
-      if constexpr (C::IPW > 1) burst1(std::integral_constant<int, 1>());
-      if constexpr (C::IPW > 2) { burst1(std::integral_constant<int, 2>()); burst1(std::integral_constant<int, 3>()); }
-      if constexpr (C::IPW > 4) {
-        burst1(std::integral_constant<int, 4>()); burst1(std::integral_constant<int, 5>());
-        burst1(std::integral_constant<int, 6>()); burst1(std::integral_constant<int, 7>());
+      if constexpr (!ASM_IDS) fetch_ids(min(KS, last), widx[KS % IDL]);
+      else if constexpr (EARLY_PERMUTE) {
+        wait_vmem_le<0>(widx[KS % IDL]);   // (arrived with the wait above; this ties the register to a wait for the compiler)
+        keys_begin(min(KS, last), widx[KS % IDL], keys[KNEW]);
       }
-      fetch_ids(min(2, last));
       wait_vmem_all();
       __syncthreads();
-      // S(0) from K slot 0; keyA/keyB end up as keys(0)/keys(1)
-      y_phase(std::integral_constant<int, 0>(), 0, SA, SA, PA, no(), yes());
+      // S(0) from K slot 0
+      y_phase(std::integral_constant<int, 0>(), 0, SA, yes());
       m_run = m_pend;   // O = 0 and l = 0 so far: the first exponent base needs no rescale
       resc = false;
       int t = 0;
-      for (; t + 1 < ntiles; t += 2) {
-        iteration(t, std::integral_constant<int, 0>(), PB, PA, SB, SA);
-        iteration(t + 1, std::integral_constant<int, 1>(), PA, PB, SA, SB);
+      for (;;) {
+#define FG_STEP(J)                                             \
+        if constexpr (U > J) {                                 \
+          if (t >= ntiles) break;                              \
+          iteration(std::integral_constant<int, J>(), t);      \
+          t++;                                                 \
+        }
+        FG_STEP(0) FG_STEP(1) FG_STEP(2) FG_STEP(3) FG_STEP(4) FG_STEP(5)
+        FG_STEP(6) FG_STEP(7) FG_STEP(8) FG_STEP(9) FG_STEP(10) FG_STEP(11)
+#undef FG_STEP
       }
-      if (t < ntiles) iteration(t, std::integral_constant<int, 0>(), PB, PA, SB, SA);
       if constexpr (WAVE_PRIO) __builtin_amdgcn_s_setprio(0);
       wait_vmem_all();
       __syncthreads();
-      if ((ntiles & 1) == 0) x_phase(std::integral_constant<int, 1>(), PB, no(), no(), SA);
-      else x_phase(std::integral_constant<int, 0>(), PA, no(), no(), SA);
+      // O += V(ntiles-1)^T P(ntiles-1)^T: the slot and the register set depend on ntiles - 1 modulo lcm(VS, 2)
+      constexpr int UD = clcm(VS, 2);
+      const int jd = (ntiles - 1) % UD;
+#define FG_DRAIN(J)                                                                                                   \
+      if constexpr (UD > J) {                                                                                          \
+        if (jd == J)                                                                                                   \
+          x_phase(std::integral_constant<int, J % VS>(), std::integral_constant<int, 0>(), std::integral_constant<int, 0>(), \
+                  std::integral_constant<int, 0>(), (J & 1) ? PB : PA, no(), no(), SA, no(), SA, PA);                 \
+      }
+      FG_DRAIN(0) FG_DRAIN(1) FG_DRAIN(2) FG_DRAIN(3) FG_DRAIN(4) FG_DRAIN(5) FG_DRAIN(6) FG_DRAIN(7)
+#undef FG_DRAIN
     }
 
     // ---------------- epilogue ----------------
@@ -791,7 +942,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
         }
       }
     }
-    // the barrier at the top of the loop (after the queue pop) separates this item's LDS use from the next
+    // this item's LDS use (tile rings, merge scratch) ends here; the next item's begins with the work-item word
     __syncthreads();
   }
   // The last workgroup to leave rewinds the queue, so a later launch can reuse the stored order
@@ -801,7 +952,7 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
     const int done = atomicAdd(a.counter + 1, 1);
     if (done == (int)gridDim.x - 1) {
       atomicExch(a.counter + 1, 0);
-      atomicExch(a.counter, 0);
+      for (int q = 0; q < 8; q++) atomicExch(a.counter + 8 + q, 0);
     }
   }
 }

@@ -8,10 +8,9 @@ namespace fg {
 template <int D>
 static int launch_d(const FwdArgs& a, int cus, hipStream_t stream) {
   static int occ[2][64];
-  constexpr int lds = FwdCfg<128, D>::LDS_BYTES;
   if (a.N == 1)
-    return launch_variant(fgattn_fwd_kernel<128, D, NMODE_N1, 2, PART_ALL, true>, lds, a, cus, stream, nullptr, occ[0]);
-  return launch_variant(fgattn_fwd_kernel<128, D, NMODE_GROUPS_SHORT, 2, PART_ALL, true>, lds, a, cus, stream, nullptr, occ[1]);
+    return launch_variant(fgattn_fwd_kernel<128, D, NMODE_N1, 2, PART_ALL, true>, fwd_lds_bytes<128, D, NMODE_N1, true>(), a, cus, stream, nullptr, occ[0]);
+  return launch_variant(fgattn_fwd_kernel<128, D, NMODE_GROUPS_SHORT, 2, PART_ALL, true>, fwd_lds_bytes<128, D, NMODE_GROUPS_SHORT, true>(), a, cus, stream, nullptr, occ[1]);
 }
 
 int launch_grouped(const FwdArgs& a, int d, int cus, hipStream_t stream) {

@@ -10,14 +10,13 @@ static_assert(FwdCfg<64, 128>::NT == (64 <= 32 ? 128 : 64 == 64 ? 64 : 32), "hos
 template <int D, int OCC>
 static int launch_d(const FwdArgs& a, int cus, hipStream_t stream, int* grid_only) {
   static int occ[4][64];
-  constexpr int lds = FwdCfg<64, D>::LDS_BYTES;
   if (a.indptr == nullptr)
-    return launch_variant(fgattn_fwd_kernel<64, D, NMODE_DENSE, OCC>, lds, a, cus, stream, grid_only, occ[0]);
+    return launch_variant(fgattn_fwd_kernel<64, D, NMODE_DENSE, OCC>, fwd_lds_bytes<64, D, NMODE_DENSE>(), a, cus, stream, grid_only, occ[0]);
   if (a.N == 1)
-    return launch_variant(fgattn_fwd_kernel<64, D, NMODE_N1, OCC>, lds, a, cus, stream, grid_only, occ[1]);
+    return launch_variant(fgattn_fwd_kernel<64, D, NMODE_N1, OCC>, fwd_lds_bytes<64, D, NMODE_N1>(), a, cus, stream, grid_only, occ[1]);
   if (a.N > 0 && a.L % a.N == 0)
-    return launch_variant(fgattn_fwd_kernel<64, D, NMODE_GROUPS, OCC>, lds, a, cus, stream, grid_only, occ[2]);
-  return launch_variant(fgattn_fwd_kernel<64, D, NMODE_GROUPS_SHORT, OCC>, lds, a, cus, stream, grid_only, occ[3]);
+    return launch_variant(fgattn_fwd_kernel<64, D, NMODE_GROUPS, OCC>, fwd_lds_bytes<64, D, NMODE_GROUPS>(), a, cus, stream, grid_only, occ[2]);
+  return launch_variant(fgattn_fwd_kernel<64, D, NMODE_GROUPS_SHORT, OCC>, fwd_lds_bytes<64, D, NMODE_GROUPS_SHORT>(), a, cus, stream, grid_only, occ[3]);
 }
 
 int launch_mt64(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only) {

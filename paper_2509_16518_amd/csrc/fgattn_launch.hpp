@@ -11,7 +11,7 @@ namespace fg {
 
 template <typename Kernel>
 int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipStream_t stream, int* grid_only,
-                   int* occ_cache) {
+                   int* occ_cache, int wgs_per_cu_cap = 0) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
   static std::mutex cache_mutex;   // one per kernel variant: first calls from several host threads take turns
@@ -25,7 +25,7 @@ int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipS
       return FGATTN_E_DEVICE;
     occ_cache[dev] = occ;
   }
-  long long want = (long long)cus * occ_cache[dev];
+  long long want = (long long)cus * (wgs_per_cu_cap > 0 && wgs_per_cu_cap < occ_cache[dev] ? wgs_per_cu_cap : occ_cache[dev]);
   lock.unlock();
 #ifdef FG_ONE_WG_PER_CU
   want = cus;

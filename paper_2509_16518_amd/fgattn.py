@@ -124,7 +124,7 @@ def fgattn_forward_static(q, k, v, mask_indptr, mask_indices, params, out, lse, 
                                        _stream_ptr(stream)))
 
 
-PART_GATHER, PART_COMPUTE = 1, 2
+PART_GATHER, PART_COMPUTE, PART_GATHER_RING3, PART_GATHER_ONE_WG = 1, 2, 3, 4
 
 
 def fgattn_forward_grouped(q, k, v, group_tiles, union_indptr, union_indices, union_members, params, out, lse, workspace,

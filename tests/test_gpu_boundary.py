@@ -71,11 +71,16 @@ def test_forward_part_is_a_measurement_aid_only(M):
     ws = prob.workspace(p)
     F.fgattn_plan(prob.d_indptr, p, ws)
     scratch_out, scratch_lse = torch.empty_like(prob.out), torch.empty_like(prob.lse)
-    for part in (F.PART_GATHER, F.PART_COMPUTE):
+    parts = (F.PART_GATHER, F.PART_COMPUTE) + ((F.PART_GATHER_RING3, F.PART_GATHER_ONE_WG) if M == 64 else ())
+    for part in parts:
         F.fgattn_forward_part(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, scratch_out, scratch_lse, ws, part)
     torch.cuda.synchronize()
-    expect(F.E_FLAGS, lambda: F.fgattn_forward_part(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, scratch_out,
-                                                    scratch_lse, ws, 3))
+    for bad in (0, 5):
+        expect(F.E_FLAGS, lambda: F.fgattn_forward_part(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, scratch_out,
+                                                        scratch_lse, ws, bad))
+    if M == 128:   # the ring / occupancy variants of the gather half are built for the 64-row tile only
+        expect(F.E_SHAPE, lambda: F.fgattn_forward_part(prob.q, prob.k, prob.v, prob.d_indptr, prob.d_indices, p, scratch_out,
+                                                        scratch_lse, ws, F.PART_GATHER_RING3))
     tiny = Problem(W.TINY)
     pt = tiny.params()
     expect(F.E_SHAPE, lambda: F.fgattn_forward_part(tiny.q, tiny.k, tiny.v, tiny.d_indptr, tiny.d_indices, pt, tiny.out,
