@@ -236,8 +236,8 @@ __global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
   constexpr bool MASK_ROWS = variant_has_mask_row(NMODE, GROUPED);   // per-key bias / membership row in LDS
   constexpr bool ASM_IDS = NMODE == NMODE_N1 && !GROUPED;            // ids through untracked loads
   // ... whose cross-lane permute is issued before the barrier that precedes its use (measured on one box: 2.4% faster
-  // at 128 query rows, 2.5% slower at 64, where a wave has twice the gathers to issue per tile and the extra wait for
-  // the ids at the end of an iteration delays the next one's)
+  // at 128 query rows, 2.5% slower at 64 -- also when the ids are requested an iteration earlier, so that the wait
+  // for them at the end of an iteration is free)
   constexpr bool EARLY_PERMUTE = ASM_IDS && MT == 128;
   static_assert(!GROUPED || (MT == 128 && (NMODE == NMODE_N1 || NMODE == NMODE_GROUPS_SHORT)),
                 "groups are 128 query rows with a sparse list (any L: the variant that masks positions past the end)");
