@@ -53,8 +53,12 @@ enum {
                                      earlier fgattn_forward/fgattn_plan call for the same mask and params */
   /* Read by the fgattn_mask_* calls only (the others ignore it): select from the rows of scores in device
    * memory even where a row fits in LDS (at most 32768 key blocks), the path that longer rows always take.
-   * Same results; it changes the workspace size, so pass the same flags to all three mask calls. */
-  FGATTN_FLAG_MASK_ROWS_IN_HBM = 8
+   * Same results; pass the same flags to all three mask calls. */
+  FGATTN_FLAG_MASK_ROWS_IN_HBM = 8,
+  /* Read by the fgattn_mask_* calls only: a score buffer of the smallest size (one tile of 128 query blocks)
+   * instead of up to 1 GiB, so that small inputs also take several chunks.  Same results; it changes the
+   * workspace size, so pass the same flags to all three mask calls. */
+  FGATTN_FLAG_MASK_ONE_TILE_CHUNKS = 16
 };
 
 typedef struct fgattn_params {
@@ -163,9 +167,13 @@ int fgattn_validate_mask(const int64_t* mask_indptr, const int32_t* mask_indices
  *
  * fgattn_mask_select: q, k as in fgattn_forward (strides from `p`; v/out strides ignored).  Writes
  *   mask_indptr (device, int64 [B*H*ceil(L/M) + 1]) and keeps the per-block cut in `workspace`
- *   (device, 256-byte aligned, at least fgattn_mask_workspace_bytes(p): block means, one fp32 score per
- *   (query block, key block), 20 bytes per query block, and one bit per (query block, key block) where
- *   a row of scores fits in LDS).  top_p must be in (0, 1] (FGATTN_E_SCALE otherwise).
+ *   (device, 256-byte aligned, at least fgattn_mask_workspace_bytes(p)).  top_p must be in (0, 1]
+ *   (FGATTN_E_SCALE otherwise).
+ *   Workspace size: the block means (2*d bytes per query block, and per key block unless B == 1 and N == 1),
+ *   20 bytes per query block, one bit per (query block, key block), and a buffer for fp32 scores that is
+ *   bounded: the scores are produced and consumed in chunks of whole tiles of 128 query blocks, and the buffer
+ *   holds min(all tiles, max(1, floor(1 GiB / tile))) tiles, a tile being 128 * 4 * ceil32(ceil(L/N)) bytes.
+ *   So it never exceeds max(1 GiB, one tile); a tile is below 1 GiB up to 2 097 152 key blocks.
  * fgattn_mask_emit: after the caller has read nnz = mask_indptr[last] and provided mask_indices (device, int32,
  *   capacity >= nnz entries): writes the kept key-block ids of every query block in ascending order.  Entries
  *   that would fall beyond `indices_capacity` are dropped, never written out of bounds.  `workspace` must be the

@@ -160,7 +160,8 @@ static int check_shape(const fgattn_params* p) {
   if ((int64_t)p->L + p->N > 0x7fffffffLL) return FGATTN_E_SHAPE;
   if (p->L > (1 << 24)) return FGATTN_E_SHAPE;   // key row * row bytes uses 24-bit multiplies
   if (n_items_of(p) > 0x7fffffffLL) return FGATTN_E_SHAPE;
-  if (p->flags & ~(FGATTN_FLAG_STATIC_ASSIGN | FGATTN_FLAG_FIFO_QUEUE | FGATTN_FLAG_REUSE_PLAN | FGATTN_FLAG_MASK_ROWS_IN_HBM))
+  if (p->flags & ~(FGATTN_FLAG_STATIC_ASSIGN | FGATTN_FLAG_FIFO_QUEUE | FGATTN_FLAG_REUSE_PLAN | FGATTN_FLAG_MASK_ROWS_IN_HBM |
+                   FGATTN_FLAG_MASK_ONE_TILE_CHUNKS))
     return FGATTN_E_FLAGS;
   return FGATTN_OK;
 }

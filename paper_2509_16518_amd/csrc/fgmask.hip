@@ -10,9 +10,13 @@
 //                      LDS; finds the CUT, the 64-bit key (score, then lower id first) of the last kept key
 //                      block, without sorting the row, and leaves the kept set as one bit per key block
 //   select_kernel      longer rows (or on request): the same selection, one workgroup per query block,
-//                      every pass reading the row from device memory; leaves only the cut
+//                      every pass reading the row from device memory; leaves the same outputs
 //   scan_kernel        counts -> indptr
-//   emit_bits_kernel / emit_kernel   kept ids, ascending, into indices (from the bit rows / from scores and cut)
+//   emit_bits_kernel   kept ids, ascending, into indices (from the bit rows)
+//
+// The scores are the only large intermediate (4 bytes per pair of query block and key block).  They are
+// produced and consumed in chunks of whole score tiles (128 query blocks of one slice), scores_kernel and
+// the selection kernel alternating over one buffer of bounded size; what outlives a chunk is one bit per pair.
 //
 // Selection works on integers so that it does not depend on the order of additions: the weight
 // of a key block is exp2((s - max) * log2 e) in 2^-40 fixed point, the row's mass Z is the integer
@@ -112,7 +116,7 @@ constexpr int kTilesPerGroup = 16;
 template <int D>
 __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const uint16_t* kp, int64_t k_slice_stride,
                                                       int64_t k_row_stride, int QB, int G, int Gs, float scale,
-                                                      float* scores, unsigned* range) {
+                                                      int unit0, int YT, float* scores, unsigned* range) {
   constexpr int STEPS = D / 16;
   constexpr int ROWB = D * 2;                 // bytes of a row of K
   constexpr int CHUNKS = ROWB / 16;           // 16-byte chunks per row
@@ -122,8 +126,11 @@ __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const u
   __shared__ __attribute__((aligned(16))) unsigned char ktile[2][TILEB];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int ln = lane & 31, g = lane >> 5;
-  const int slice = blockIdx.z;
-  const int q0 = blockIdx.y * 128 + wv * 32;   // (a wave past the last query block still helps with the tiles)
+  // blockIdx.y names a score tile of this chunk: unit = slice * YT + (tile of 128 query blocks inside the slice)
+  const int unit = unit0 + blockIdx.y;
+  const int slice = unit / YT;
+  const int qtile0 = (unit - slice * YT) * 128;
+  const int q0 = qtile0 + wv * 32;   // (a wave past the last query block still helps with the tiles)
   const int tile0 = blockIdx.x * kTilesPerGroup;
   auto swz = [](int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
   bf16x8 qf[STEPS];
@@ -180,7 +187,7 @@ __global__ void __launch_bounds__(256) scores_kernel(const uint16_t* qp, const u
         const float v = acc[r] * scale;
         vmax[r] = fmaxf(vmax[r], v);
         vmin[r] = fminf(vmin[r], v);
-        if (qrow < QB) scores[((int64_t)slice * QB + qrow) * Gs + col] = v;
+        if (qrow < QB) scores[((int64_t)blockIdx.y * 128 + (qrow - qtile0)) * Gs + col] = v;
       }
     }
     if (t + 1 < ntiles) stash_tile((t + 1) & 1);   // (the buffer that was read in step t - 1, before the last barrier)
@@ -422,32 +429,30 @@ __device__ __forceinline__ void sort_candidates(SH& sh, int n2) {
 }
 
 // Selection for one query block (row of scores `s`, in device memory or in LDS); called by all threads of the
-// workgroup.  ROW_IN_LDS: also writes the kept set as one bit per key block (`keep_bits`, Gw words per row).
+// workgroup.  Writes the cut, the count and the kept set as one bit per key block (`keep_bits`, Gw words per row).
 template <int THREADS, int BINS, int CAP, bool ROW_IN_LDS, typename SH>
 __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, float rmax, float rmin, int G, float top_p,
                                            unsigned long long* cut, unsigned* count, uint32_t* keep_bits, int Gw) {
   constexpr bool WITH_CNT = !ROW_IN_LDS;
   const int tid = threadIdx.x;
-  // ROW_IN_LDS, at the end (all threads; the cut is in sh.cut): one bit per key block, set where its rank key is
-  // not below the cut.  A thread ranks four consecutive key blocks, eight lanes make a word.
+  // At the end (all threads; the cut is in sh.cut): one bit per key block, set where its rank key is not below
+  // the cut.  A thread ranks four consecutive key blocks, eight lanes make a word.
   auto write_bits = [&]() {
-    if constexpr (ROW_IN_LDS) {
-      __syncthreads();
-      const unsigned long long c = sh.cut;
-      for (int base = 0; base < Gw * 32; base += THREADS * 4) {
-        const int j4 = base + tid * 4;
-        unsigned nib = 0;
-        if (j4 < G) {
-          const float4 v = *reinterpret_cast<const float4*>(s + j4);
-          nib = (rank_key(v.x, j4) >= c ? 1u : 0u) | (j4 + 1 < G && rank_key(v.y, j4 + 1) >= c ? 2u : 0u) |
-                (j4 + 2 < G && rank_key(v.z, j4 + 2) >= c ? 4u : 0u) | (j4 + 3 < G && rank_key(v.w, j4 + 3) >= c ? 8u : 0u);
-        }
-        unsigned word = nib << (4 * (tid & 7));
-        word |= __shfl_xor(word, 1);
-        word |= __shfl_xor(word, 2);
-        word |= __shfl_xor(word, 4);
-        if ((tid & 7) == 0 && (j4 >> 5) < Gw) keep_bits[row * Gw + (j4 >> 5)] = word;
+    __syncthreads();
+    const unsigned long long c = sh.cut;
+    for (int base = 0; base < Gw * 32; base += THREADS * 4) {
+      const int j4 = base + tid * 4;
+      unsigned nib = 0;
+      if (j4 < G) {
+        const float4 v = *reinterpret_cast<const float4*>(s + j4);
+        nib = (rank_key(v.x, j4) >= c ? 1u : 0u) | (j4 + 1 < G && rank_key(v.y, j4 + 1) >= c ? 2u : 0u) |
+              (j4 + 2 < G && rank_key(v.z, j4 + 2) >= c ? 4u : 0u) | (j4 + 3 < G && rank_key(v.w, j4 + 3) >= c ? 8u : 0u);
       }
+      unsigned word = nib << (4 * (tid & 7));
+      word |= __shfl_xor(word, 1);
+      word |= __shfl_xor(word, 2);
+      word |= __shfl_xor(word, 4);
+      if ((tid & 7) == 0 && (j4 >> 5) < Gw) keep_bits[row * Gw + (j4 >> 5)] = word;
     }
   };
 
@@ -696,31 +701,50 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
   write_bits();
 }
 
+// Row `local` of a chunk's score buffer that starts at score tile unit0: the (slice, query block) row it holds, or
+// -1 for the unused rows of a slice's last tile.
+__device__ __forceinline__ int64_t chunk_row(int64_t local, int unit0, int YT, int QB) {
+  const int unit = unit0 + (int)(local >> 7);
+  const int slice = unit / YT;
+  const int qb = (unit - slice * YT) * 128 + (int)(local & 127);
+  return qb < QB ? (int64_t)slice * QB + qb : -1;
+}
+
 // One workgroup per query block, rows read from device memory in every pass.
 template <int THREADS, int BINS, int CAP>
-__global__ void __launch_bounds__(THREADS) select_kernel(const float* scores, const unsigned* range, int G, int Gs,
-                                                         float top_p, unsigned long long* cut, unsigned* count) {
+__global__ void __launch_bounds__(THREADS) select_kernel(const float* scores, const unsigned* range, int unit0, int YT, int QB,
+                                                         int G, int Gs, float top_p, unsigned long long* cut, unsigned* count,
+                                                         uint32_t* keep_bits, int Gw) {
   __shared__ SelShared<THREADS, BINS, CAP, true> sh;
-  const int64_t row = blockIdx.x;
-  select_row<THREADS, BINS, CAP, false>(sh, scores + row * Gs, row, from_ordered(range[2 * row]),
-                                        from_ordered(range[2 * row + 1]), G, top_p, cut, count, nullptr, 0);
+  const int64_t local = blockIdx.x;
+  const int64_t row = chunk_row(local, unit0, YT, QB);
+  if (row < 0) return;
+  select_row<THREADS, BINS, CAP, false>(sh, scores + local * Gs, row, from_ordered(range[2 * row]),
+                                        from_ordered(range[2 * row + 1]), G, top_p, cut, count, keep_bits, Gw);
 }
 
 // Rows of at most kRowLdsFloats scores: persistent workgroups (one per compute unit: a row takes most of the
 // LDS).  A row is read from device memory once, into registers while the row before it is being processed,
 // then copied to dynamic LDS, and every pass runs on that copy.
 template <int THREADS, int BINS, int CAP>
-__global__ void __launch_bounds__(THREADS) select_lds_kernel(const float* scores, const unsigned* range, int64_t rows,
-                                                             int G, int Gs, float top_p, unsigned long long* cut,
-                                                             unsigned* count, uint32_t* keep_bits, int Gw) {
+__global__ void __launch_bounds__(THREADS) select_lds_kernel(const float* scores, const unsigned* range, int64_t chunk_rows,
+                                                             int unit0, int YT, int QB, int G, int Gs, float top_p,
+                                                             unsigned long long* cut, unsigned* count, uint32_t* keep_bits,
+                                                             int Gw) {
   static_assert(THREADS * 4 * 8 == kRowLdsFloats, "eight float4 per thread cover the largest row");
   __shared__ SelShared<THREADS, BINS, CAP, false> sh;
   extern __shared__ __attribute__((aligned(16))) float row_lds[];
   const int tid = threadIdx.x;
   float4 st[8];
   unsigned r_hi = 0, r_lo = 0;
-  auto fetch = [&](int64_t row) {
-    const float* s = scores + row * Gs;
+  // the next buffer row at or after `local` (in steps of the grid) that holds a query block; chunk_rows if none
+  auto next_used = [&](int64_t local) {
+    while (local < chunk_rows && chunk_row(local, unit0, YT, QB) < 0) local += gridDim.x;
+    return local;
+  };
+  auto fetch = [&](int64_t local) {
+    const float* s = scores + local * Gs;
+    const int64_t row = chunk_row(local, unit0, YT, QB);
     r_hi = range[2 * row];
     r_lo = range[2 * row + 1];
 #pragma unroll
@@ -729,9 +753,9 @@ __global__ void __launch_bounds__(THREADS) select_lds_kernel(const float* scores
       st[i] = j4 < Gs ? *reinterpret_cast<const float4*>(s + j4) : float4{0.0f, 0.0f, 0.0f, 0.0f};
     }
   };
-  int64_t row = blockIdx.x;
-  if (row < rows) fetch(row);
-  for (; row < rows; row += gridDim.x) {
+  int64_t local = next_used(blockIdx.x);
+  if (local < chunk_rows) fetch(local);
+  while (local < chunk_rows) {
     __syncthreads();   // the row before this one has been read for the last time
 #pragma unroll
     for (int i = 0; i < 8; i++) {
@@ -740,8 +764,11 @@ __global__ void __launch_bounds__(THREADS) select_lds_kernel(const float* scores
     }
     const float rmax = from_ordered(r_hi), rmin = from_ordered(r_lo);
     __syncthreads();
-    if (row + gridDim.x < rows) fetch(row + gridDim.x);
-    select_row<THREADS, BINS, CAP, true>(sh, row_lds, row, rmax, rmin, G, top_p, cut, count, keep_bits, Gw);
+    const int64_t next = next_used(local + gridDim.x);
+    if (next < chunk_rows) fetch(next);
+    select_row<THREADS, BINS, CAP, true>(sh, row_lds, chunk_row(local, unit0, YT, QB), rmax, rmin, G, top_p, cut, count,
+                                         keep_bits, Gw);
+    local = next;
   }
 }
 
@@ -772,47 +799,7 @@ __global__ void __launch_bounds__(1024) scan_kernel(const unsigned* count, int64
   }
 }
 
-// ids whose rank key is not below the cut, in ascending order
-__global__ void __launch_bounds__(kSelThreads) emit_kernel(const float* scores, int G, int Gs,
-                                                           const unsigned long long* cut, const int64_t* indptr,
-                                                           int32_t* indices, int64_t capacity) {
-  __shared__ unsigned wave_tot[4];
-  const int tid = threadIdx.x;
-  const int64_t row = blockIdx.x;
-  const float* s = scores + row * Gs;
-  const unsigned long long c = cut[row];
-  const int64_t out0 = indptr[row];
-  unsigned run = 0;
-  constexpr int STEP = kSelThreads * 4;
-  const float4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-  float4 nxt[3];   // the next three chunks are in flight while this one is ranked and written
-#pragma unroll
-  for (int i = 0; i < 3; i++) nxt[i] = i * STEP + tid * 4 < G ? *reinterpret_cast<const float4*>(s + i * STEP + tid * 4) : zero4;
-  for (int base = 0; base < G; base += STEP) {
-    const int j4 = base + tid * 4;
-    const float4 v = nxt[0];
-    nxt[0] = nxt[1];
-    nxt[1] = nxt[2];
-    nxt[2] = j4 + 3 * STEP < G ? *reinterpret_cast<const float4*>(s + j4 + 3 * STEP) : zero4;
-    bool keep[4] = {false, false, false, false};
-    if (j4 < G) {
-      keep[0] = rank_key(v.x, j4) >= c;
-      keep[1] = j4 + 1 < G && rank_key(v.y, j4 + 1) >= c;
-      keep[2] = j4 + 2 < G && rank_key(v.z, j4 + 2) >= c;
-      keep[3] = j4 + 3 < G && rank_key(v.w, j4 + 3) >= c;
-    }
-    unsigned total;
-    int64_t pos = out0 + run + block_exclusive<kSelThreads>((unsigned)keep[0] + keep[1] + keep[2] + keep[3], wave_tot, &total);
-    for (int e = 0; e < 4; e++)
-      if (keep[e]) {
-        if (pos < capacity) indices[pos] = j4 + e;
-        pos++;
-      }
-    run += total;
-  }
-}
-
-// The same from the bit rows that the LDS-row selection leaves: 256 words (8192 key blocks) per step, ids
+// Kept ids in ascending order, from the bit rows that the selection leaves: 256 words (8192 key blocks) per step, ids
 // collected in LDS in ascending order and written out as one contiguous stretch.
 __global__ void __launch_bounds__(kSelThreads) emit_bits_kernel(const uint32_t* keep_bits, int Gw, const int64_t* indptr,
                                                                 int32_t* indices, int64_t capacity) {
@@ -844,8 +831,12 @@ __global__ void __launch_bounds__(kSelThreads) emit_bits_kernel(const uint32_t* 
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
+// The score buffer takes whole tiles of 128 query-block rows; as many tiles as fit kScoreBudget, at least one.
+constexpr size_t kScoreBudget = (size_t)1 << 30;
+
 struct Layout {
   int64_t rows, QB, G, Gs, Gw, slices;
+  int64_t YT, units, chunk_units;   // score tiles per slice, in all, and per chunk
   bool row_in_lds;   // rows of scores fit the LDS-row selection kernel
   size_t qp_off, kp_off, scores_off, cut_off, count_off, range_off, bits_off, total;
 };
@@ -858,7 +849,7 @@ static int layout_of(const fgattn_params* p, Layout* lo) {
   if (p->d != 64 && p->d != 128) return FGATTN_E_SHAPE;
   if (p->M != 16 && p->M != 32 && p->M != 64 && p->M != 128) return FGATTN_E_SHAPE;
   if (p->L > (1 << 24)) return FGATTN_E_SHAPE;
-  if (p->flags & ~15) return FGATTN_E_FLAGS;
+  if (p->flags & ~31) return FGATTN_E_FLAGS;
   lo->slices = (int64_t)p->B * p->H;
   lo->QB = ((int64_t)p->L + p->M - 1) / p->M;
   lo->G = ((int64_t)p->L + p->N - 1) / p->N;
@@ -867,13 +858,20 @@ static int layout_of(const fgattn_params* p, Layout* lo) {
   lo->row_in_lds = lo->Gs <= kRowLdsFloats && !(p->flags & FGATTN_FLAG_MASK_ROWS_IN_HBM);
   lo->rows = lo->slices * lo->QB;
   if (lo->rows > 0x7fffffffLL || lo->slices > 65535) return FGATTN_E_SHAPE;
+  lo->YT = (lo->QB + 127) / 128;
+  lo->units = lo->slices * lo->YT;
+  const size_t tile_bytes = (size_t)128 * lo->Gs * 4;
+  lo->chunk_units = (p->flags & FGATTN_FLAG_MASK_ONE_TILE_CHUNKS) ? 1 : (int64_t)(kScoreBudget / tile_bytes);
+  if (lo->chunk_units < 1) lo->chunk_units = 1;
+  if (lo->chunk_units > 65535) lo->chunk_units = 65535;   // (a chunk's tiles are the y dimension of a grid)
+  if (lo->chunk_units > lo->units) lo->chunk_units = lo->units;
   size_t off = 0;
   lo->qp_off = off;
   off = align256(off + (size_t)lo->rows * p->d * 2);
   lo->kp_off = off;
   if (p->N > 1 || p->B > 1) off = align256(off + (size_t)lo->slices * lo->G * p->d * 2);   // else K is read in place
   lo->scores_off = off;
-  off = align256(off + (size_t)lo->rows * lo->Gs * 4);
+  off = align256(off + (size_t)lo->chunk_units * tile_bytes);
   lo->cut_off = off;
   off = align256(off + (size_t)lo->rows * 8);
   lo->count_off = off;
@@ -881,7 +879,7 @@ static int layout_of(const fgattn_params* p, Layout* lo) {
   lo->range_off = off;
   off = align256(off + (size_t)lo->rows * 8);
   lo->bits_off = off;
-  if (lo->row_in_lds) off = align256(off + (size_t)lo->rows * lo->Gw * 4);
+  off = align256(off + (size_t)lo->rows * lo->Gw * 4);
   lo->total = off;
   return FGATTN_OK;
 }
@@ -960,34 +958,42 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
     k_slice_stride = lo.G * p->d;
     k_row_stride = p->d;
   }
-  const dim3 sgrid((unsigned)((lo.G + kTilesPerGroup * 32 - 1) / (kTilesPerGroup * 32)), (unsigned)((lo.QB + 127) / 128),
-                   (unsigned)lo.slices);
-  if (p->d == 128)
-    hipLaunchKernelGGL(scores_kernel<128>, sgrid, dim3(256), 0, stream, qp, kmat, k_slice_stride, k_row_stride, (int)lo.QB,
-                       (int)lo.G, (int)lo.Gs, p->scale, scores, range);
-  else
-    hipLaunchKernelGGL(scores_kernel<64>, sgrid, dim3(256), 0, stream, qp, kmat, k_slice_stride, k_row_stride, (int)lo.QB,
-                       (int)lo.G, (int)lo.Gs, p->scale, scores, range);
-  if (!launched()) return FGATTN_E_DEVICE;
+  uint32_t* keep_bits = reinterpret_cast<uint32_t*>(ws + lo.bits_off);
+  auto lds_kern = select_lds_kernel<kRowThreads, kRowBins, kRowCap>;
   if (lo.row_in_lds) {
-    auto kern = select_lds_kernel<kRowThreads, kRowBins, kRowCap>;
     static bool lds_set[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
     if (!lds_set[dev]) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(lds_kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               kRowLdsFloats * 4) != hipSuccess)
         return FGATTN_E_DEVICE;
       lds_set[dev] = true;
     }
-    const unsigned wgs = (unsigned)(lo.rows < cus ? lo.rows : cus);
-    hipLaunchKernelGGL(kern, dim3(wgs), dim3(kRowThreads), (size_t)lo.Gs * 4, stream, scores, range, lo.rows, (int)lo.G,
-                       (int)lo.Gs, top_p, cut, count, reinterpret_cast<uint32_t*>(ws + lo.bits_off), (int)lo.Gw);
-  } else {
-    hipLaunchKernelGGL((select_kernel<kSelThreads, kBins, kCap>), dim3((unsigned)lo.rows), dim3(kSelThreads), 0, stream,
-                       scores, range, (int)lo.G, (int)lo.Gs, top_p, cut, count);
   }
-  if (!launched()) return FGATTN_E_DEVICE;
+  const unsigned gx = (unsigned)((lo.G + kTilesPerGroup * 32 - 1) / (kTilesPerGroup * 32));
+  for (int64_t unit0 = 0; unit0 < lo.units; unit0 += lo.chunk_units) {
+    const int64_t nunits = lo.units - unit0 < lo.chunk_units ? lo.units - unit0 : lo.chunk_units;
+    const int64_t chunk_rows = nunits * 128;
+    const dim3 sgrid(gx, (unsigned)nunits);
+    if (p->d == 128)
+      hipLaunchKernelGGL(scores_kernel<128>, sgrid, dim3(256), 0, stream, qp, kmat, k_slice_stride, k_row_stride, (int)lo.QB,
+                         (int)lo.G, (int)lo.Gs, p->scale, (int)unit0, (int)lo.YT, scores, range);
+    else
+      hipLaunchKernelGGL(scores_kernel<64>, sgrid, dim3(256), 0, stream, qp, kmat, k_slice_stride, k_row_stride, (int)lo.QB,
+                         (int)lo.G, (int)lo.Gs, p->scale, (int)unit0, (int)lo.YT, scores, range);
+    if (!launched()) return FGATTN_E_DEVICE;
+    if (lo.row_in_lds) {
+      const unsigned wgs = (unsigned)(chunk_rows < cus ? chunk_rows : cus);
+      hipLaunchKernelGGL(lds_kern, dim3(wgs), dim3(kRowThreads), (size_t)lo.Gs * 4, stream, scores, range, chunk_rows,
+                         (int)unit0, (int)lo.YT, (int)lo.QB, (int)lo.G, (int)lo.Gs, top_p, cut, count, keep_bits, (int)lo.Gw);
+    } else {
+      hipLaunchKernelGGL((select_kernel<kSelThreads, kBins, kCap>), dim3((unsigned)chunk_rows), dim3(kSelThreads), 0, stream,
+                         scores, range, (int)unit0, (int)lo.YT, (int)lo.QB, (int)lo.G, (int)lo.Gs, top_p, cut, count, keep_bits,
+                         (int)lo.Gw);
+    }
+    if (!launched()) return FGATTN_E_DEVICE;
+  }
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, count, lo.rows, mask_indptr);
   return launched() ? FGATTN_OK : FGATTN_E_DEVICE;
 }
@@ -1005,15 +1011,9 @@ int fgattn_mask_emit(const fgattn_params* p, const int64_t* mask_indptr, int32_t
   rc = device_ok();
   if (rc) return rc;
   const char* ws = static_cast<const char*>(workspace);
-  const float* scores = reinterpret_cast<const float*>(ws + lo.scores_off);
-  const unsigned long long* cut = reinterpret_cast<const unsigned long long*>(ws + lo.cut_off);
-  if (lo.row_in_lds)
-    hipLaunchKernelGGL(emit_bits_kernel, dim3((unsigned)lo.rows), dim3(kSelThreads), 0, static_cast<hipStream_t>(stream_v),
-                       reinterpret_cast<const uint32_t*>(ws + lo.bits_off), (int)lo.Gw, mask_indptr, mask_indices,
-                       indices_capacity);
-  else
-    hipLaunchKernelGGL(emit_kernel, dim3((unsigned)lo.rows), dim3(kSelThreads), 0, static_cast<hipStream_t>(stream_v), scores,
-                       (int)lo.G, (int)lo.Gs, cut, mask_indptr, mask_indices, indices_capacity);
+  hipLaunchKernelGGL(emit_bits_kernel, dim3((unsigned)lo.rows), dim3(kSelThreads), 0, static_cast<hipStream_t>(stream_v),
+                     reinterpret_cast<const uint32_t*>(ws + lo.bits_off), (int)lo.Gw, mask_indptr, mask_indices,
+                     indices_capacity);
   return launched() ? FGATTN_OK : FGATTN_E_DEVICE;
 }
 

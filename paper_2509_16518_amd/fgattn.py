@@ -20,7 +20,7 @@ class FgattnParams(ctypes.Structure):
                 ("scale", ctypes.c_float), ("flags", ctypes.c_int32)]
 
 
-FLAG_STATIC_ASSIGN, FLAG_FIFO_QUEUE, FLAG_REUSE_PLAN, FLAG_MASK_ROWS_IN_HBM = 1, 2, 4, 8
+FLAG_STATIC_ASSIGN, FLAG_FIFO_QUEUE, FLAG_REUSE_PLAN, FLAG_MASK_ROWS_IN_HBM, FLAG_MASK_ONE_TILE_CHUNKS = 1, 2, 4, 8, 16
 E_NULL, E_SHAPE, E_STRIDE, E_ALIGN, E_WORKSPACE, E_SCALE, E_DEVICE, E_MASK, E_FLAGS, E_STATIC_LIMIT = range(-1, -11, -1)
 STATIC_MAX_ITEMS = 65536
 

@@ -43,7 +43,7 @@ def test_workspace_bytes_and_shape_validation(lib):
     p = F.FgattnParams(1, 12, 32760, 128, 64, 1, *([0] * 12), 0.1, 0)
     n = lib.fgattn_workspace_bytes(ctypes.byref(p))
     assert n >= 256 + 4 * 12 * 512 and n % 256 == 0
-    for field, bad in (("d", 96), ("M", 24), ("N", 0), ("L", 0), ("H", 0), ("flags", 16)):
+    for field, bad in (("d", 96), ("M", 24), ("N", 0), ("L", 0), ("H", 0), ("flags", 32)):
         q = F.FgattnParams(1, 12, 32760, 128, 64, 1, *([0] * 12), 0.1, 0)
         setattr(q, field, bad)
         assert lib.fgattn_workspace_bytes(ctypes.byref(q)) == 0, field
@@ -106,3 +106,21 @@ def test_build_rejects_a_foreign_m0_write(tmp_path):
     bad.write_text("\ts_mov_b32 m0, s5 ; fg_m0\n\ts_mov_b32 m0, s9\n")
     with pytest.raises(RuntimeError, match="M0 is touched"):
         build.check_m0_writes(str(bad))
+
+
+def test_mask_workspace_is_bounded(lib):
+    # the fp32 scores pass through a buffer of at most 1 GiB (whole tiles of 128 query blocks); what grows with the
+    # problem is one bit per pair of query block and key block, the block means and 20 bytes per query block
+    lib.fgattn_mask_workspace_bytes.restype = ctypes.c_size_t
+    def nbytes(H, L, M, flags=0):
+        p = F.FgattnParams(1, H, L, 128, M, 1, *([0] * 12), 0.1, flags)
+        return lib.fgattn_mask_workspace_bytes(ctypes.byref(p))
+    def small_parts(H, L, M):
+        rows, G = H * -(-L // M), L
+        return rows * 128 * 2 + rows * 20 + rows * -(-G // 32) * 4
+    GiB = 1 << 30
+    wan, hun = nbytes(12, 32760, 64), nbytes(24, 118800, 128)
+    assert 12 * 512 * 32768 * 4 <= wan <= 12 * 512 * 32768 * 4 + small_parts(12, 32760, 64) + 4096    # one chunk: all scores
+    assert hun <= GiB + small_parts(24, 118800, 128) + 4096 and hun >= GiB - 128 * 118816 * 4
+    one_tile = nbytes(24, 118800, 128, F.FLAG_MASK_ONE_TILE_CHUNKS)
+    assert 128 * 118816 * 4 <= one_tile <= 128 * 118816 * 4 + small_parts(24, 118800, 128) + 4096

@@ -80,7 +80,9 @@ def check_rows(oracle, w, q_bits, k_bits, top_p, indptr, indices, rows, scale=No
                                           (128, 32, 128, 1024, (4, 16, 16)), (32, 1, 128, 1000, (10, 10, 10)),
                                           (64, 3, 64, 1000, (10, 10, 10)), (16, 1, 64, 3000, (3, 25, 40))])
 @pytest.mark.parametrize("top_p", [0.5, 0.9])
-@pytest.mark.parametrize("flags", [0, F.FLAG_MASK_ROWS_IN_HBM], ids=["lds-rows", "hbm-rows"])
+@pytest.mark.parametrize("flags", [0, F.FLAG_MASK_ROWS_IN_HBM, F.FLAG_MASK_ONE_TILE_CHUNKS,
+                                   F.FLAG_MASK_ROWS_IN_HBM | F.FLAG_MASK_ONE_TILE_CHUNKS],
+                         ids=["lds-rows", "hbm-rows", "lds-rows-chunked", "hbm-rows-chunked"])
 def test_mask_matches_oracle_small(oracle_mod, M, N, d, L, grid, top_p, flags):
     w = W.Workload("mask-M%d-N%d-d%d-L%d" % (M, N, d, L), H=2, L=L, d=d, M=M, N=N, grid=grid, seed=4000 + M + N)
     q, k = W.make_qk_local(w, gain=1.5 if d == 64 else 1.2)
@@ -104,6 +106,7 @@ def test_mask_unstructured_inputs(oracle_mod):
 
 @pytest.mark.parametrize("L,N,top_p,kept,flags", [(1024, 8, 0.75, 96, 0), (8192, 1, 0.75, 6144, 0), (8192, 1, 0.5, 4096, 0),
                                                   (1024, 8, 0.75, 96, 8), (8192, 1, 0.5, 4096, 8),
+                                                  (8192, 1, 0.5, 4096, 16), (40000, 1, 0.625, 25000, 16),
                                                   (40000, 1, 0.625, 25000, 0), (32768, 1, 0.5, 16384, 0),
                                                   (32767, 1, 0.5, 16384, 0), (32769, 1, 0.5, 16385, 0)])
 def test_uniform_scores_closed_form(L, N, top_p, kept, flags):
@@ -224,8 +227,9 @@ def test_mask_full_size_wan(oracle_mod):
 
 
 def test_mask_full_size_hunyuan(oracle_mod):
-    # config-4 shape: 22296 query blocks x 118800 key blocks (10.6 GB of scores); rows this long are selected from
-    # device memory.  Sampled rows against the oracle, all rows by the validator.
+    # config-4 shape: 22296 query blocks x 118800 key blocks (10.6 GB of scores, passed through a 1 GiB buffer in
+    # eleven chunks); rows this long are selected from device memory.  Sampled rows against the oracle, all rows
+    # by the validator.
     w = W.HUNYUAN
     q, k = W.make_qk_local(w, gain=2.5)
     say("mask hunyuan p=0.9")
