@@ -311,6 +311,8 @@ def main():
         for name in ("wan-14b-skew", "hunyuan"):
             log("extra config %s" % name)
             res["configs"][name] = extra_config(named[name], 5)
+    from paper_2509_16518_amd.build import source_id
+    res["source"] = source_id()
     print(json.dumps(res), flush=True)
 
 

@@ -64,3 +64,29 @@ def build_hip(force=True, extra_flags=()):
             os.remove(os.path.join(objdir, f))   # other intermediates of -save-temps
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIBFGATTN])
     return LIBFGATTN
+
+
+def source_id():
+    """What a measurement script prints so that its table can be tied to a tree: the git commit if this is a
+    checkout (with '+' if tracked files differ from it), and a digest of the kernel and generator sources, which can
+    be recomputed from any copy of the files."""
+    import hashlib
+    head = "unknown"
+    try:
+        r = subprocess.run(["git", "-C", REPO_DIR, "rev-parse", "--short=12", "HEAD"], stdout=subprocess.PIPE,
+                           stderr=subprocess.DEVNULL, text=True)
+        if r.returncode == 0 and r.stdout.strip():
+            head = r.stdout.strip()
+            d = subprocess.run(["git", "-C", REPO_DIR, "status", "--porcelain", "--untracked-files=no"],
+                               stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True)
+            if d.returncode == 0 and d.stdout.strip():
+                head += "+"
+    except OSError:
+        pass
+    h = hashlib.sha256()
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".hpp"))]
+    files += [os.path.join(REPO_DIR, "include", "fgattn.h"), os.path.join(PKG_DIR, "workloads", "fgw_gen.c")]
+    for path in files:
+        with open(path, "rb") as f:
+            h.update(os.path.basename(path).encode() + b"\0" + f.read())
+    return {"git_head": head, "source_sha256": h.hexdigest()[:16]}

@@ -27,6 +27,8 @@ def main():
     if not torch.cuda.is_available():
         print("no GPU visible", file=sys.stderr)
         sys.exit(2)
+    from .build import source_id
+    print(json.dumps(dict(source_id(), script="paper_2509_16518_amd.config_table", argv=sys.argv[1:])), flush=True)
 
     def dev(bits):
         return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
