@@ -6,9 +6,10 @@
 // Kernels (all on the caller's stream):
 //   pool_kernel        block means (fp32 running sum in row order, fp32 divide, one bf16 rounding)
 //   scores_kernel      S = scale * Q_avg K_avg^T with bf16 MFMA, fp32 scores to the workspace
-//   select_lds_kernel  rows of up to 32768 scores: persistent workgroups, the row of a query block held in
-//                      LDS; finds the CUT, the 64-bit key (score, then lower id first) of the last kept key
-//                      block, without sorting the row, and leaves the kept set as one bit per key block
+//   select_bins_kernel rows of up to 32768 scores: persistent 512-thread workgroups, two per compute unit; the
+//                      row is read once, the bin of every score stays in LDS as 16 bits; finds the CUT, the 64-bit
+//                      key (score, then lower id first) of the last kept key block, without sorting the row, and
+//                      leaves the kept set as one bit per key block
 //   select_kernel      longer rows (or on request): the same selection, one workgroup per query block,
 //                      every pass reading the row from device memory; leaves the same outputs
 //   scan_kernel        counts -> indptr
@@ -28,6 +29,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "fgattn.h"
 
 namespace fgm {
@@ -39,11 +42,12 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 constexpr int kSelThreads = 256;
 constexpr int kBins = 2048;
 constexpr int kCap = 2048;          // members of the crossing bin that are sorted in LDS
-// Rows of up to kRowLdsFloats scores are selected by a 1024-thread workgroup that keeps the row in LDS.
-constexpr int kRowThreads = 1024;
-constexpr int kRowBins = 2048;
-constexpr int kRowCap = 1024;
-constexpr int kRowLdsFloats = 32768;
+// Rows of up to kRowBinsMax scores are selected by 512-thread workgroups that read the row once and keep the bin
+// of every score in LDS.
+constexpr int kRowThreads = 512;
+constexpr int kRowBins = 1024;
+constexpr int kRowCap = 512;
+constexpr int kRowBinsMax = 32768;
 constexpr float kLog2e = 1.44269504088896340736f;
 
 __device__ __forceinline__ unsigned ordered_bits(float s) {   // monotone: larger score, larger unsigned
@@ -281,21 +285,46 @@ __device__ __forceinline__ unsigned block_exclusive(unsigned n, unsigned* wave_t
   return before + incl - n;
 }
 
-// WITH_CNT: the histogram also counts the members of every bin.  Without, the counts are taken by a pass of
-// their own after the bin is known (one LDS atomic per score fewer; only worth it where re-reading the row is cheap).
-template <int THREADS, int BINS, int CAP, bool WITH_CNT>
+// Visits every score of a row once, ONE score per lane and step: consecutive lanes hold consecutive key blocks, so
+// a wave-wide vote on a property of the score is the bit pattern of 64 consecutive key blocks.  fn(v, j, valid) is
+// called by all lanes of every wave together, also for positions past the end of the row (valid = j < G), so that
+// it may vote; four steps are in flight.
+template <int THREADS, typename Fn>
+__device__ __forceinline__ void for_each_score_by_lane(const float* s, int G, Fn&& fn) {
+  const int tid = threadIdx.x;
+  int base = 0;
+  for (; base + 3 * THREADS < G; base += 4 * THREADS) {
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int j = base + i * THREADS + tid;
+      v[i] = j < G ? s[j] : 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int j = base + i * THREADS + tid;
+      fn(v[i], j, j < G);
+    }
+  }
+  for (; base < G; base += THREADS) {
+    const int j = base + tid;
+    fn(j < G ? s[j] : 0.0f, j, j < G);
+  }
+}
+
+template <int THREADS, int BINS, int CAP>
 struct SelShared {
   unsigned long long mass[BINS];
-  unsigned cnt[WITH_CNT ? BINS : THREADS / 64];
-  unsigned long long cand[CAP];
+  unsigned wave_tot[THREADS / 64];
+  alignas(16) unsigned long long cand[CAP];
   unsigned long long wave_m[THREADS / 64];
   unsigned wave_n[THREADS / 64];
   unsigned long long mass_above, target, cut;
   unsigned n_above, bin, bin_cnt, ncand, klo, khi;
 };
 
-template <int THREADS, int BINS, int CAP, bool WITH_CNT>
-__device__ __forceinline__ unsigned long long block_sum_u64(SelShared<THREADS, BINS, CAP, WITH_CNT>& sh, unsigned long long v) {
+template <int THREADS, int BINS, int CAP>
+__device__ __forceinline__ unsigned long long block_sum_u64(SelShared<THREADS, BINS, CAP>& sh, unsigned long long v) {
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
   if ((threadIdx.x & 63) == 0) sh.wave_m[threadIdx.x >> 6] = v;
   __syncthreads();
@@ -305,61 +334,42 @@ __device__ __forceinline__ unsigned long long block_sum_u64(SelShared<THREADS, B
   return r;
 }
 
-// Exclusive prefixes, in thread order, of a mass and a count; *tm gets the mass of all threads.  Contains two barriers.
-template <int THREADS, int BINS, int CAP, bool WITH_CNT>
-__device__ __forceinline__ void block_exclusive_mass(SelShared<THREADS, BINS, CAP, WITH_CNT>& sh, unsigned long long m, unsigned n,
-                                                     unsigned long long* em, unsigned* en, unsigned long long* tm) {
+// Exclusive prefix, in thread order, of a mass; *tm gets the mass of all threads.  Contains two barriers.
+template <int THREADS, int BINS, int CAP>
+__device__ __forceinline__ void block_exclusive_mass(SelShared<THREADS, BINS, CAP>& sh, unsigned long long m,
+                                                     unsigned long long* em, unsigned long long* tm) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   unsigned long long im = m;
-  unsigned in = n;
   for (int off = 1; off < 64; off <<= 1) {
     const unsigned long long um = __shfl_up(im, off);
-    const unsigned un = __shfl_up(in, off);
-    if (lane >= off) {
-      im += um;
-      in += un;
-    }
+    if (lane >= off) im += um;
   }
-  if (lane == 63) {
-    sh.wave_m[wv] = im;
-    sh.wave_n[wv] = in;
-  }
+  if (lane == 63) sh.wave_m[wv] = im;
   __syncthreads();
   unsigned long long bm = 0;
-  unsigned bn = 0;
-  for (int w2 = 0; w2 < wv; w2++) {
-    bm += sh.wave_m[w2];
-    bn += sh.wave_n[w2];
-  }
+  for (int w2 = 0; w2 < wv; w2++) bm += sh.wave_m[w2];
   unsigned long long all = bm;
   for (int w2 = wv; w2 < THREADS / 64; w2++) all += sh.wave_m[w2];
   *tm = all;
   __syncthreads();
   *em = bm + im - m;
-  *en = bn + in - n;
 }
 
 // Finds, in the histogram just built, the bin where the running mass (starting from mass_above) reaches the
-// target; updates mass_above / n_above to exclude that bin and stores bin / bin_cnt (n_above and bin_cnt only
-// WITH_CNT).  Every thread owns BINS / THREADS consecutive bins; a prefix over the threads names the one owner
-// whose bins contain the crossing.  FIRST: the histogram is that of the whole row; its mass Z sets the target
-// ceil(top_p * Z) (at least 1, at most Z), and nothing lies above it yet.
-template <bool FIRST, int THREADS, int BINS, int CAP, bool WITH_CNT>
-__device__ __forceinline__ void locate_bin(SelShared<THREADS, BINS, CAP, WITH_CNT>& sh, float top_p) {
+// target; updates mass_above to exclude that bin and stores the bin.  Every thread owns BINS / THREADS consecutive
+// bins; a prefix over the threads names the one owner whose bins contain the crossing.  FIRST: the histogram is
+// that of the whole row; its mass Z sets the target ceil(top_p * Z) (at least 1, at most Z), and nothing lies above
+// it yet.
+template <bool FIRST, int THREADS, int BINS, int CAP>
+__device__ __forceinline__ void locate_bin(SelShared<THREADS, BINS, CAP>& sh, float top_p) {
   const int tid = threadIdx.x;
   constexpr int PER = BINS / THREADS;
   const unsigned long long base = FIRST ? 0ull : sh.mass_above;
   unsigned long long target = FIRST ? 0ull : sh.target;
-  const unsigned n_base = FIRST ? 0u : sh.n_above;
   unsigned long long local = 0;
-  unsigned nlocal = 0;
-  for (int i = 0; i < PER; i++) {
-    local += sh.mass[tid * PER + i];
-    if constexpr (WITH_CNT) nlocal += sh.cnt[tid * PER + i];
-  }
+  for (int i = 0; i < PER; i++) local += sh.mass[tid * PER + i];
   unsigned long long em, Z;
-  unsigned en;
-  block_exclusive_mass(sh, local, nlocal, &em, &en, &Z);
+  block_exclusive_mass(sh, local, &em, &Z);
   if constexpr (FIRST) {   // every thread computes the same target
     const double t = ceil((double)top_p * (double)Z);
     target = t < 1.0 ? 1ull : (unsigned long long)t;
@@ -371,11 +381,9 @@ __device__ __forceinline__ void locate_bin(SelShared<THREADS, BINS, CAP, WITH_CN
   const bool mine = (lo < target && (target <= lo + local || tid == THREADS - 1)) || (tid == 0 && target <= lo);
   if (mine) {
     unsigned long long run = lo;
-    unsigned n = n_base + en;
     int b = tid * PER;
     while (b < tid * PER + PER - 1 && run + sh.mass[b] < target) {
       run += sh.mass[b];
-      if constexpr (WITH_CNT) n += sh.cnt[b];
       b++;
     }
     sh.mass_above = run;
@@ -384,33 +392,15 @@ __device__ __forceinline__ void locate_bin(SelShared<THREADS, BINS, CAP, WITH_CN
       sh.target = target;
       sh.n_above = 0;
     }
-    if constexpr (WITH_CNT) {
-      sh.n_above = n;
-      sh.bin_cnt = sh.cnt[b];
-    }
   }
   __syncthreads();
 }
 
-// Sorts cand[0 .. n2) (n2 a power of two, unused entries zero) by descending key.  Up to 64 keys: one wave, in
-// registers; more: the whole workgroup, in LDS.  All threads call it; it ends with a barrier.
+// Sorts cand[0 .. n2) (n2 a power of two above 64, unused entries zero) by descending key in LDS.  All threads call
+// it; it ends with a barrier.
 template <int THREADS, typename SH>
 __device__ __forceinline__ void sort_candidates(SH& sh, int n2) {
   const int tid = threadIdx.x;
-  if (n2 <= 64) {
-    if (tid < 64) {
-      unsigned long long x = tid < n2 ? sh.cand[tid] : 0ull;
-      for (int k = 2; k <= 64; k <<= 1)
-        for (int jj = k >> 1; jj > 0; jj >>= 1) {
-          const unsigned long long y = __shfl_xor(x, jj);
-          const bool keep_max = ((tid & jj) == 0) == ((tid & k) == 0);   // lower lane of a descending pair, or upper of an ascending
-          x = keep_max ? (x > y ? x : y) : (x < y ? x : y);
-        }
-      if (tid < n2) sh.cand[tid] = x;   // zeros rank last, so the first n2 lanes hold what was there, sorted
-    }
-    __syncthreads();
-    return;
-  }
   for (int k = 2; k <= n2; k <<= 1)
     for (int jj = k >> 1; jj > 0; jj >>= 1) {
       for (int i = tid; i < n2; i += THREADS) {
@@ -430,14 +420,19 @@ __device__ __forceinline__ void sort_candidates(SH& sh, int n2) {
 
 // Selection for one query block (row of scores `s`, in device memory or in LDS); called by all threads of the
 // workgroup.  Writes the cut, the count and the kept set as one bit per key block (`keep_bits`, Gw words per row).
-template <int THREADS, int BINS, int CAP, bool ROW_IN_LDS, typename SH>
+//
+// Passes over the row: (1) histogram of mass over the score range; (2) one score per lane: the scores ranked above
+// the crossing bin are counted and, through wave votes, written as bits straight away, the bin's members are
+// collected; then the members are ranked, and the bits of those at or above the cut are added.  Only a crossing bin
+// with more members than the sort holds takes further passes, and a last one that writes all bits from the cut.
+template <int THREADS, int BINS, int CAP, typename SH>
 __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, float rmax, float rmin, int G, float top_p,
                                            unsigned long long* cut, unsigned* count, uint32_t* keep_bits, int Gw) {
-  constexpr bool WITH_CNT = !ROW_IN_LDS;
-  const int tid = threadIdx.x;
-  // At the end (all threads; the cut is in sh.cut): one bit per key block, set where its rank key is not below
-  // the cut.  A thread ranks four consecutive key blocks, eight lanes make a word.
-  auto write_bits = [&]() {
+  const int tid = threadIdx.x, lane = tid & 63;
+  uint32_t* const bits_row = keep_bits + row * Gw;
+  // All bits of the row from the cut (in sh.cut): set where the rank key is not below it.  A thread ranks four
+  // consecutive key blocks, eight lanes make a word.
+  auto write_all_bits = [&]() {
     __syncthreads();
     const unsigned long long c = sh.cut;
     for (int base = 0; base < Gw * 32; base += THREADS * 4) {
@@ -452,7 +447,23 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
       word |= __shfl_xor(word, 1);
       word |= __shfl_xor(word, 2);
       word |= __shfl_xor(word, 4);
-      if ((tid & 7) == 0 && (j4 >> 5) < Gw) keep_bits[row * Gw + (j4 >> 5)] = word;
+      if ((tid & 7) == 0 && (j4 >> 5) < Gw) bits_row[j4 >> 5] = word;
+    }
+  };
+  // The bits of everything above the crossing bin are in memory already (pass 2): add those of the collected
+  // members cand[0 .. n) that are at or above the cut.  Those stores were made by other waves of this workgroup:
+  // every wave waits until its own have completed before the barrier, so the atomics on the same words, which go to
+  // the same L2, come after them (a device-wide fence would do too, but writes back the whole L2 on this chip).
+  auto add_member_bits = [&](unsigned n) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const unsigned long long c = sh.cut;
+    for (unsigned i = tid; i < n; i += THREADS) {
+      const unsigned long long key = sh.cand[i];
+      if (key >= c) {
+        const unsigned id = 0xFFFFFFFFu - (unsigned)key;
+        atomicOr(&bits_row[id >> 5], 1u << (id & 31));
+      }
     }
   };
 
@@ -464,58 +475,61 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
     return b < 0 ? 0 : (b > BINS - 1 ? BINS - 1 : b);
   };
 
-  // pass 2: mass of the row and its histogram over the score range
-  for (int i = tid; i < BINS; i += THREADS) {
-    sh.mass[i] = 0;
-    if constexpr (WITH_CNT) sh.cnt[i] = 0;
-  }
+  // pass 1: mass of the row and its histogram over the score range
+  for (int i = tid; i < BINS; i += THREADS) sh.mass[i] = 0;
   __syncthreads();
-  for_each_score<THREADS>(s, G, [&](float v, int) {
-    const int b = value_bin(v);
-    atomicAdd(&sh.mass[b], weight_of(v, rmax));
-    if constexpr (WITH_CNT) atomicAdd(&sh.cnt[b], 1u);
-  });
+  for_each_score<THREADS>(s, G, [&](float v, int) { atomicAdd(&sh.mass[value_bin(v)], weight_of(v, rmax)); });
   __syncthreads();
   locate_bin<true>(sh, top_p);
 
-  // Without counts in the histogram (the row is in LDS, passes are cheap): one pass that counts the scores
-  // ranked above the crossing bin and collects the rank keys of its members, as many as fit the sort.
-  // cls(v): -1 above the bin, 0 inside, +1 below or outside what was the bin before.
-  auto count_and_collect = [&](auto&& cls) {
+  // One pass, one score per lane: counts the scores ranked above the crossing bin and collects the rank keys of
+  // its members, as many as fit the sort.  cls(v): -1 above the bin, 0 inside, +1 below or outside what was the
+  // bin before.  WITH_BITS: a wave's vote on "above" is the bit pattern of 64 consecutive key blocks, i.e. two words
+  // of the row's bits, which lanes 0 and 1 store (every word of the row is written once, by the wave that owns it).
+  auto count_and_collect = [&](auto&& cls, auto with_bits) {
     if (tid == 0) sh.ncand = 0;
     __syncthreads();
-    unsigned na = 0;
-    for_each_score<THREADS>(s, G, [&](float v, int j) {
-      const int c = cls(v);
-      if (c < 0) na++;
+    unsigned na = 0;   // the same in every lane of a wave
+    for_each_score_by_lane<THREADS>(s, G, [&](float v, int j, bool valid) {
+      const int c = valid ? cls(v) : 1;
+      const unsigned long long above = __ballot(c < 0);
+      na += (unsigned)__popcll(above);
+      if constexpr (decltype(with_bits)::value) {
+        const int word = ((j - lane) >> 5) + lane;   // (j - lane: the wave's first key block, a multiple of 64)
+        if (lane < 2 && word < Gw) bits_row[word] = lane ? (uint32_t)(above >> 32) : (uint32_t)above;
+      }
       if (c == 0) {
         const unsigned pos = atomicAdd(&sh.ncand, 1u);
         if (pos < (unsigned)CAP) sh.cand[pos] = rank_key(v, j);
       }
     });
-    const unsigned long long na_all = block_sum_u64(sh, (unsigned long long)na);   // (its barriers also order the atomics before the read of ncand)
+    const unsigned long long na_all = block_sum_u64(sh, lane == 0 ? (unsigned long long)na : 0ull);   // (its barriers also order the atomics before the read of ncand)
     if (tid == 0) {
       sh.n_above += (unsigned)na_all;
       sh.bin_cnt = sh.ncand;
     }
     __syncthreads();
   };
-  if constexpr (!WITH_CNT) {
+  {
     const int b0 = (int)sh.bin;
-    count_and_collect([&](float v) {
-      const int b = value_bin(v);
-      return b < b0 ? -1 : (b == b0 ? 0 : 1);
-    });
+    count_and_collect(
+        [&](float v) {
+          const int b = value_bin(v);
+          return b < b0 ? -1 : (b == b0 ? 0 : 1);
+        },
+        std::true_type{});
   }
 
   // The members of the crossing bin form a contiguous stretch of the ranking.  While there are too many to
   // sort, narrow the stretch: take the range [klo, khi] of their ordered score bits and histogram it again,
   // now linearly in those bits (every round divides the range by BINS, so a few rounds reach a single value).
   bool by_value = true;     // how the current bin is defined: value_bin() == bin, or key range [klo, khi]
+  bool bits_partial = true; // the bits in memory are those of pass 2 (everything above the first crossing bin)
   unsigned klo = 0, khi = 0;
   for (int round = 0; round < 6; round++) {
     const unsigned bin = sh.bin;
     if (sh.bin_cnt <= (unsigned)CAP) break;
+    bits_partial = false;   // members of the first bin get ranked above the final one: all bits are rewritten at the end
     // range of ordered bits inside the current bin
     if (tid == 0) {
       sh.klo = 0xFFFFFFFFu;
@@ -539,17 +553,13 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
     by_value = false;
     if (klo == khi) break;   // one score value left: a run of equal scores, handled by id below
     const unsigned long long R = (unsigned long long)(khi - klo) + 1ull;
-    for (int i = tid; i < BINS; i += THREADS) {
-      sh.mass[i] = 0;
-      if constexpr (WITH_CNT) sh.cnt[i] = 0;
-    }
+    for (int i = tid; i < BINS; i += THREADS) sh.mass[i] = 0;
     __syncthreads();
     for_each_score<THREADS>(s, G, [&](float v, int) {
       const unsigned o = ordered_bits(v);
       if (o >= klo && o <= khi) {
         const int b = (int)(((unsigned long long)(khi - o) * BINS) / R);
         atomicAdd(&sh.mass[b], weight_of(v, rmax));
-        if constexpr (WITH_CNT) atomicAdd(&sh.cnt[b], 1u);
       }
     });
     __syncthreads();
@@ -560,59 +570,51 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
     const unsigned long long d_hi = ((b + 1) * R + BINS - 1) / BINS - 1;
     const unsigned nkhi = khi - (unsigned)d_lo;
     const unsigned nklo = khi - (unsigned)(d_hi > (unsigned long long)(khi - klo) ? (khi - klo) : d_hi);
-    if constexpr (!WITH_CNT) {
-      const unsigned old_hi = khi;
-      count_and_collect([&](float v) {
-        const unsigned o = ordered_bits(v);
-        return (o > nkhi && o <= old_hi) ? -1 : ((o >= nklo && o <= nkhi) ? 0 : 1);
-      });
-    }
+    const unsigned old_hi = khi;
+    count_and_collect(
+        [&](float v) {
+          const unsigned o = ordered_bits(v);
+          return (o > nkhi && o <= old_hi) ? -1 : ((o >= nklo && o <= nkhi) ? 0 : 1);
+        },
+        std::false_type{});
     khi = nkhi;
     klo = nklo;
     __syncthreads();
   }
 
-  const unsigned bin = sh.bin;
   const unsigned bin_cnt = sh.bin_cnt;
+  auto finish_bits = [&]() {
+    if (bits_partial)
+      add_member_bits(bin_cnt);
+    else
+      write_all_bits();
+  };
   if (bin_cnt == 0) {   // unreachable (the crossing bin has mass, hence members); kept so that no path leaves the outputs unset
     if (tid == 0) {
       sh.cut = ~0ull;
       cut[row] = ~0ull;
       count[row] = sh.n_above;
     }
-    write_bits();
+    finish_bits();
     return;
   }
   if (bin_cnt <= (unsigned)CAP) {
-    // sort the members of the crossing bin by rank key (descending) and walk their masses
-    int n2 = 1;
-    while (n2 < (int)bin_cnt) n2 <<= 1;
-    if constexpr (WITH_CNT) {
-      if (tid == 0) sh.ncand = 0;
-      for (int i = tid; i < n2; i += THREADS) sh.cand[i] = 0ull;
-      __syncthreads();
-      for_each_score<THREADS>(s, G, [&, bin, by_value, klo, khi](float v, int j) {
-        const unsigned o = ordered_bits(v);
-        const bool in = by_value ? (value_bin(v) == (int)bin) : (o >= klo && o <= khi);
-        if (in) {
-          const unsigned pos = atomicAdd(&sh.ncand, 1u);
-          if (pos < (unsigned)CAP) sh.cand[pos] = rank_key(v, j);
-        }
-      });
-    } else {
-      for (int i = (int)bin_cnt + tid; i < n2; i += THREADS) sh.cand[i] = 0ull;   // the members are there already
-    }
-    __syncthreads();
+    // rank the members of the crossing bin (they are in cand[0 .. bin_cnt)) and walk their masses
     if (bin_cnt <= 64u) {
-      // few members (the usual case): the first wave ranks them by counting, orders their masses by rank and
-      // finds the crossing with a prefix over its lanes
+      // few members (the usual case): the first wave holds one each, ranks them by counting (the keys are
+      // distinct), orders their masses by rank through LDS and finds the crossing with a prefix over its lanes
       if (tid < 64) {
         const int n = (int)bin_cnt;
         const unsigned long long key = tid < n ? sh.cand[tid] : 0ull;
+        const unsigned key_lo = (unsigned)key, key_hi = (unsigned)(key >> 32);
         int rank = 0;
-        for (int j = 0; j < n; j++) rank += sh.cand[j] > key ? 1 : 0;   // keys are distinct
+        for (int j = 0; j < n; j++) {
+          const unsigned long long other = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)key_hi, j) << 32) |
+                                           (unsigned)__builtin_amdgcn_readlane((int)key_lo, j);
+          rank += other > key ? 1 : 0;
+        }
         if (tid < n) {
-          sh.mass[rank] = weight_of(from_ordered((unsigned)(key >> 32)), rmax);
+          sh.mass[rank] = weight_of(from_ordered(key_hi), rmax);
           sh.mass[64 + rank] = key;
         }
         unsigned long long inc = tid < n ? sh.mass[tid] : 0ull;   // (same wave: LDS accesses complete in order)
@@ -629,9 +631,13 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
           count[row] = sh.n_above + (unsigned)idx + 1u;
         }
       }
-      write_bits();
+      finish_bits();
       return;
     }
+    int n2 = 128;
+    while (n2 < (int)bin_cnt) n2 <<= 1;
+    for (int i = (int)bin_cnt + tid; i < n2; i += THREADS) sh.cand[i] = 0ull;
+    __syncthreads();
     sort_candidates<THREADS>(sh, n2);
     // first position where mass_above + (masses of cand[0..position]) reaches the target: every thread owns
     // CAP / THREADS consecutive candidates, a prefix over the threads names the owner of the crossing
@@ -644,9 +650,8 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
       if (idx <= lastc) local += weight_of(from_ordered((unsigned)(sh.cand[idx] >> 32)), rmax);
     }
     unsigned long long em;
-    unsigned en;
     unsigned long long all;
-    block_exclusive_mass(sh, local, 0u, &em, &en, &all);
+    block_exclusive_mass(sh, local, &em, &all);
     const unsigned long long lo = base + em;
     // (the second clause names the last candidate if the masses fell short of the target, the third the first
     // one if the target was already reached; neither happens with a consistent histogram)
@@ -664,7 +669,7 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
       cut[row] = sh.cand[idx];
       count[row] = sh.n_above + (unsigned)idx + 1u;
     }
-    write_bits();
+    finish_bits();
     return;
   }
 
@@ -688,7 +693,7 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
       in[3] = j4 + 3 < G && ordered_bits(v.w) == klo;
     }
     unsigned total;
-    unsigned pos = run + block_exclusive<THREADS>((unsigned)in[0] + in[1] + in[2] + in[3], sh.cnt, &total);
+    unsigned pos = run + block_exclusive<THREADS>((unsigned)in[0] + in[1] + in[2] + in[3], sh.wave_tot, &total);
 #pragma unroll
     for (int e = 0; e < 4; e++)
       if (in[e] && (unsigned long long)(++pos) == t_keep) {
@@ -698,7 +703,7 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
       }
     run += total;
   }
-  write_bits();
+  write_all_bits();   // (this path is only reached through the narrowing rounds)
 }
 
 // Row `local` of a chunk's score buffer that starts at score tile unit0: the (slice, query block) row it holds, or
@@ -715,60 +720,211 @@ template <int THREADS, int BINS, int CAP>
 __global__ void __launch_bounds__(THREADS) select_kernel(const float* scores, const unsigned* range, int unit0, int YT, int QB,
                                                          int G, int Gs, float top_p, unsigned long long* cut, unsigned* count,
                                                          uint32_t* keep_bits, int Gw) {
-  __shared__ SelShared<THREADS, BINS, CAP, true> sh;
+  __shared__ SelShared<THREADS, BINS, CAP> sh;
   const int64_t local = blockIdx.x;
   const int64_t row = chunk_row(local, unit0, YT, QB);
   if (row < 0) return;
-  select_row<THREADS, BINS, CAP, false>(sh, scores + local * Gs, row, from_ordered(range[2 * row]),
+  select_row<THREADS, BINS, CAP>(sh, scores + local * Gs, row, from_ordered(range[2 * row]),
                                         from_ordered(range[2 * row + 1]), G, top_p, cut, count, keep_bits, Gw);
 }
 
-// Rows of at most kRowLdsFloats scores: persistent workgroups (one per compute unit: a row takes most of the
-// LDS).  A row is read from device memory once, into registers while the row before it is being processed,
-// then copied to dynamic LDS, and every pass runs on that copy.
+// Rows of at most kRowBinsMax scores: the row is read from device memory ONCE.  That pass builds the mass histogram
+// and leaves, in LDS, the bin of every score as 16 bits; the second pass then works on those alone (one per lane:
+// bin < crossing bin -> the key block is kept, and a wave's vote is two words of the bit row; bin == crossing bin ->
+// a member, whose score is fetched again by id).  64 KB of bins + the histogram + the members let two 512-thread
+// workgroups share a compute unit, so the short barrier-separated phases of one row hide under the passes of
+// another; the workgroups are persistent and take rows in turn.  A crossing bin with more members than fit is
+// rare and handed to select_row, which starts that row over from device memory.
 template <int THREADS, int BINS, int CAP>
-__global__ void __launch_bounds__(THREADS) select_lds_kernel(const float* scores, const unsigned* range, int64_t chunk_rows,
-                                                             int unit0, int YT, int QB, int G, int Gs, float top_p,
-                                                             unsigned long long* cut, unsigned* count, uint32_t* keep_bits,
-                                                             int Gw) {
-  static_assert(THREADS * 4 * 8 == kRowLdsFloats, "eight float4 per thread cover the largest row");
-  __shared__ SelShared<THREADS, BINS, CAP, false> sh;
-  extern __shared__ __attribute__((aligned(16))) float row_lds[];
-  const int tid = threadIdx.x;
-  float4 st[8];
-  unsigned r_hi = 0, r_lo = 0;
-  // the next buffer row at or after `local` (in steps of the grid) that holds a query block; chunk_rows if none
-  auto next_used = [&](int64_t local) {
-    while (local < chunk_rows && chunk_row(local, unit0, YT, QB) < 0) local += gridDim.x;
-    return local;
+struct alignas(16) BinsShared {
+  SelShared<THREADS, BINS, CAP> sel;
+  // the same memory serves the general path when a row is handed over (it needs no 16-bit bins)
+  union {
+    uint16_t bins[kRowBinsMax];
+    SelShared<THREADS, kBins, kCap> general;
   };
-  auto fetch = [&](int64_t local) {
-    const float* s = scores + local * Gs;
+};
+
+template <int THREADS, int BINS, int CAP>
+__global__ void __launch_bounds__(THREADS) select_bins_kernel(const float* scores, const unsigned* range, int64_t chunk_rows,
+                                                              int unit0, int YT, int QB, int G, int Gs, float top_p,
+                                                              unsigned long long* cut, unsigned* count, uint32_t* keep_bits,
+                                                              int Gw) {
+  static_assert(CAP == THREADS, "one member per thread in the ranking");
+  static_assert(BINS >= 128 && BINS % THREADS == 0 && BINS <= 65535, "bins");
+  __shared__ BinsShared<THREADS, BINS, CAP> shm;
+  auto& sh = shm.sel;
+  const int tid = threadIdx.x, lane = tid & 63;
+  for (int64_t local = blockIdx.x; local < chunk_rows; local += gridDim.x) {
     const int64_t row = chunk_row(local, unit0, YT, QB);
-    r_hi = range[2 * row];
-    r_lo = range[2 * row + 1];
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-      const int j4 = (i * THREADS + tid) * 4;
-      st[i] = j4 < Gs ? *reinterpret_cast<const float4*>(s + j4) : float4{0.0f, 0.0f, 0.0f, 0.0f};
-    }
-  };
-  int64_t local = next_used(blockIdx.x);
-  if (local < chunk_rows) fetch(local);
-  while (local < chunk_rows) {
-    __syncthreads();   // the row before this one has been read for the last time
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-      const int j4 = (i * THREADS + tid) * 4;
-      if (j4 < Gs) *reinterpret_cast<float4*>(row_lds + j4) = st[i];
-    }
-    const float rmax = from_ordered(r_hi), rmin = from_ordered(r_lo);
+    if (row < 0) continue;   // (the same for all threads)
+    const float* s = scores + local * Gs;
+    const float rmax = from_ordered(range[2 * row]), rmin = from_ordered(range[2 * row + 1]);
+    uint32_t* const bits_row = keep_bits + row * Gw;
+    const float width = rmax - rmin;
+    const float inv = width > 0.0f ? (float)BINS / width : 0.0f;
+    auto value_bin = [&](float v) -> int {   // bin 0 holds the largest scores
+      const int b = (int)((rmax - v) * inv);
+      return b < 0 ? 0 : (b > BINS - 1 ? BINS - 1 : b);
+    };
+    __syncthreads();   // the row before this one is done with the shared state
+    for (int i = tid; i < BINS; i += THREADS) sh.mass[i] = 0;
+    if (tid == 0) sh.ncand = 0;
     __syncthreads();
-    const int64_t next = next_used(local + gridDim.x);
-    if (next < chunk_rows) fetch(next);
-    select_row<THREADS, BINS, CAP, true>(sh, row_lds, chunk_row(local, unit0, YT, QB), rmax, rmin, G, top_p, cut, count,
-                                         keep_bits, Gw);
-    local = next;
+
+    // pass 1: four consecutive scores per thread and step, four steps in flight; positions past the end get bin
+    // 0xFFFF (below every bin)
+    {
+      constexpr int STEP = THREADS * 4;
+      auto one = [&](float v, bool valid) -> unsigned {
+        if (!valid) return 0xFFFFu;
+        const int b = value_bin(v);
+        atomicAdd(&sh.mass[b], weight_of(v, rmax));
+        return (unsigned)b;
+      };
+      auto four = [&](const float4& v, int j4) {
+        const unsigned b0 = one(v.x, true), b1 = one(v.y, j4 + 1 < G), b2 = one(v.z, j4 + 2 < G), b3 = one(v.w, j4 + 3 < G);
+        *reinterpret_cast<uint2*>(&shm.bins[j4]) = uint2{b0 | (b1 << 16), b2 | (b3 << 16)};
+      };
+      // groups of four steps; the loads of the next group are in flight while this one is processed
+      const float4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+      auto load4 = [&](float4 (&x)[4], int j0) {
+#pragma unroll
+        for (int e = 0; e < 4; e++) x[e] = j0 + e * STEP < G ? *reinterpret_cast<const float4*>(s + j0 + e * STEP) : zero4;
+      };
+      float4 cur[4], nxt[4];
+      int j4 = tid * 4;
+      load4(cur, j4);
+      for (; j4 < G; j4 += 4 * STEP) {   // (no barrier inside: threads may leave at different trip counts)
+        load4(nxt, j4 + 4 * STEP);
+#pragma unroll
+        for (int e = 0; e < 4; e++)
+          if (j4 + e * STEP < G) four(cur[e], j4 + e * STEP);
+#pragma unroll
+        for (int e = 0; e < 4; e++) cur[e] = nxt[e];
+      }
+    }
+    __syncthreads();
+    locate_bin<true>(sh, top_p);
+
+    // pass 2 on the bins: one per lane and step, consecutive lanes consecutive key blocks, so that the compare
+    // "bin above the crossing bin" of a wave IS the bit pattern of 64 key blocks.  A wave owns a contiguous stretch
+    // of the row (per_wave key blocks, a multiple of 64), collects its words in two registers (step i -> lanes 2i,
+    // 2i+1) and stores them as two contiguous runs at the end.
+    {
+      const unsigned b0 = sh.bin;
+      const int wv = tid >> 6;
+      const int per_wave = ((G + THREADS - 1) / THREADS) * 64;       // <= 4096: at most 64 steps
+      const int k0 = wv * per_wave;                                  // first key block of this wave
+      const int steps = min(per_wave >> 6, max(0, (G - k0 + 63) >> 6));   // of this wave (the same in all lanes)
+      unsigned na = 0;                                               // the same in every lane of a wave
+      uint32_t acc[2] = {0u, 0u};
+      auto one = [&](unsigned b, int i) {
+        const int j = k0 + i * 64 + lane;
+        const bool valid = j < G;
+        const unsigned long long above = __ballot(valid && b < b0);
+        na += (unsigned)__popcll(above);
+        const int r = i >> 5, l2 = (i & 31) * 2;
+        // (lane l2 of the register gets the low word, lane l2 + 1 the high word; value and lane select are scalars)
+        // (two scalar registers cannot both go through the constant bus: the lane select travels in M0)
+        const int sel = __builtin_amdgcn_readfirstlane(l2);
+        const uint32_t lo_w = __builtin_amdgcn_readfirstlane((uint32_t)above), hi_w = __builtin_amdgcn_readfirstlane((uint32_t)(above >> 32));
+        asm volatile("s_mov_b32 m0, %2 ; fg_m0\n\tv_writelane_b32 %0, %1, m0 ; fg_m0" : "+v"(acc[r]) : "s"(lo_w), "s"(sel) : "m0");
+        asm volatile("s_mov_b32 m0, %2 ; fg_m0\n\tv_writelane_b32 %0, %1, m0 ; fg_m0" : "+v"(acc[r]) : "s"(hi_w), "s"(sel + 1) : "m0");
+        if (valid && b == b0) {
+          const unsigned pos = atomicAdd(&sh.ncand, 1u);
+          if (pos < (unsigned)CAP) sh.cand[pos] = (unsigned long long)(unsigned)j;
+        }
+      };
+      // (indices stay below kRowBinsMax: k0 + 64 * steps <= G rounded up to 64)
+      auto half = [&](int r, int i0, int i1) {   // steps [i0, i1) of register r: compile-time register, four reads in flight
+        int i = i0;
+        for (; i + 3 < i1; i += 4) {
+          unsigned b[4];
+#pragma unroll
+          for (int e = 0; e < 4; e++) b[e] = shm.bins[k0 + (i + e) * 64 + lane];
+#pragma unroll
+          for (int e = 0; e < 4; e++) one(b[e], i + e);
+        }
+        for (; i < i1; i++) one(shm.bins[k0 + i * 64 + lane], i);
+        (void)r;
+      };
+      half(0, 0, min(steps, 32));
+      half(1, 32, steps);
+      const int w0 = k0 >> 5;   // first word of this wave
+#pragma unroll
+      for (int r = 0; r < 2; r++) {
+        const int word = w0 + 64 * r + lane;
+        if (lane < 2 * (steps - 32 * r) && word < Gw) bits_row[word] = acc[r];
+      }
+      const unsigned long long na_all = block_sum_u64(sh, lane == 0 ? (unsigned long long)na : 0ull);   // (its barriers also order the atomics before the read of ncand)
+      if (tid == 0) sh.n_above = (unsigned)na_all;
+    }
+    const unsigned n = sh.ncand;   // (read by all threads after the barriers of the sum)
+    if (n > (unsigned)CAP) {
+      // too many members for one ranking: the general path takes the row from the start (it rewrites all outputs)
+      __syncthreads();
+      select_row<THREADS, kBins, kCap>(shm.general, s, row, rmax, rmin, G, top_p, cut, count, keep_bits, Gw);
+      continue;
+    }
+    // the members: thread i holds member i -- rank key from the score, fetched again by id
+    unsigned long long key = 0ull;
+    if (tid < (int)n) {
+      const unsigned id = (unsigned)sh.cand[tid];
+      key = rank_key(s[id], (int)id);
+    }
+    __syncthreads();   // all ids read
+    if (tid < (((int)n + 7) & ~7)) sh.cand[tid] = key;   // (zeros up to a multiple of eight: they rank below every key)
+    __syncthreads();
+    // rank by counting (the keys are distinct), masses ordered by rank through LDS, crossing by a prefix over the threads
+    int rank = 0;
+    if (tid < (int)n)
+      for (unsigned j = 0; j < n; j += 8) {   // eight keys per step: four 16-byte reads in flight
+        unsigned long long o[8];
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const ulonglong2 two = *reinterpret_cast<const ulonglong2*>(&sh.cand[j + e]);
+          o[e] = two.x;
+          o[e + 1] = two.y;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; e++) rank += o[e] > key ? 1 : 0;
+      }
+    __syncthreads();   // all of cand read: the ordered keys go back into it
+    if (tid < (int)n) {
+      sh.cand[rank] = key;
+      sh.mass[rank] = weight_of(from_ordered((unsigned)(key >> 32)), rmax);
+    }
+    __syncthreads();
+    {
+      const unsigned long long w = tid < (int)n ? sh.mass[tid] : 0ull;
+      unsigned long long before, all;
+      block_exclusive_mass(sh, w, &before, &all);
+      const unsigned long long target = sh.target, base = sh.mass_above;
+      // the first member at which the running mass reaches the target; the last one if the masses fell short (they do
+      // not with a consistent histogram)
+      const bool here = tid < (int)n && ((base + before < target && base + before + w >= target) ||
+                                         (tid == (int)n - 1 && base + before + w < target) || (tid == 0 && base >= target));
+      if (here) {
+        sh.cut = sh.cand[tid];
+        cut[row] = sh.cand[tid];
+        count[row] = sh.n_above + (unsigned)tid + 1u;
+      }
+      if (n == 0 && tid == 0) {   // unreachable (the crossing bin has mass, hence members); no output is left unset
+        sh.cut = ~0ull;
+        cut[row] = ~0ull;
+        count[row] = sh.n_above;
+      }
+    }
+    // The bits of everything above the crossing bin are in memory (pass 2), stored by other waves of this workgroup:
+    // every wave waits until its own stores have completed before the barrier, so the atomics on the same words,
+    // which go to the same L2, come after them.  Members at or above the cut are kept too.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid < (int)n && key >= sh.cut) {
+      const unsigned id = 0xFFFFFFFFu - (unsigned)key;
+      atomicOr(&bits_row[id >> 5], 1u << (id & 31));
+    }
   }
 }
 
@@ -855,7 +1011,7 @@ static int layout_of(const fgattn_params* p, Layout* lo) {
   lo->G = ((int64_t)p->L + p->N - 1) / p->N;
   lo->Gs = (lo->G + 31) & ~(int64_t)31;   // rows start on 128-byte lines
   lo->Gw = (lo->G + 31) / 32;
-  lo->row_in_lds = lo->Gs <= kRowLdsFloats && !(p->flags & FGATTN_FLAG_MASK_ROWS_IN_HBM);
+  lo->row_in_lds = lo->Gs <= kRowBinsMax && !(p->flags & FGATTN_FLAG_MASK_ROWS_IN_HBM);
   lo->rows = lo->slices * lo->QB;
   if (lo->rows > 0x7fffffffLL || lo->slices > 65535) return FGATTN_E_SHAPE;
   lo->YT = (lo->QB + 127) / 128;
@@ -959,18 +1115,6 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
     k_row_stride = p->d;
   }
   uint32_t* keep_bits = reinterpret_cast<uint32_t*>(ws + lo.bits_off);
-  auto lds_kern = select_lds_kernel<kRowThreads, kRowBins, kRowCap>;
-  if (lo.row_in_lds) {
-    static bool lds_set[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
-    if (!lds_set[dev]) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(lds_kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kRowLdsFloats * 4) != hipSuccess)
-        return FGATTN_E_DEVICE;
-      lds_set[dev] = true;
-    }
-  }
   const unsigned gx = (unsigned)((lo.G + kTilesPerGroup * 32 - 1) / (kTilesPerGroup * 32));
   for (int64_t unit0 = 0; unit0 < lo.units; unit0 += lo.chunk_units) {
     const int64_t nunits = lo.units - unit0 < lo.chunk_units ? lo.units - unit0 : lo.chunk_units;
@@ -984,8 +1128,8 @@ int fgattn_mask_select(const void* q, const void* k, const fgattn_params* p, flo
                          (int)lo.G, (int)lo.Gs, p->scale, (int)unit0, (int)lo.YT, scores, range);
     if (!launched()) return FGATTN_E_DEVICE;
     if (lo.row_in_lds) {
-      const unsigned wgs = (unsigned)(chunk_rows < cus ? chunk_rows : cus);
-      hipLaunchKernelGGL(lds_kern, dim3(wgs), dim3(kRowThreads), (size_t)lo.Gs * 4, stream, scores, range, chunk_rows,
+      const unsigned wgs = (unsigned)(chunk_rows < 2 * cus ? chunk_rows : 2 * cus);   // two fit a compute unit
+      hipLaunchKernelGGL((select_bins_kernel<kRowThreads, kRowBins, kRowCap>), dim3(wgs), dim3(kRowThreads), 0, stream, scores, range, chunk_rows,
                          (int)unit0, (int)lo.YT, (int)lo.QB, (int)lo.G, (int)lo.Gs, top_p, cut, count, keep_bits, (int)lo.Gw);
     } else {
       hipLaunchKernelGGL((select_kernel<kSelThreads, kBins, kCap>), dim3((unsigned)chunk_rows), dim3(kSelThreads), 0, stream,

@@ -107,6 +107,40 @@ def test_pooling_closed_forms(oracle_mod):
     assert W.bf16_bits_to_f64(oracle_mod.pool(w, 2)).reshape(-1).tolist() == [2.0, 20.0]
 
 
+def _bf16_nearest_even_from_f64(x):
+    """One rounding of fp64 values to bf16 bits (nearest, ties to even): the nearest of the three bf16 values around
+    the fp32-rounded candidate."""
+    c = W.f32_to_bf16_bits(x.astype(np.float32)).astype(np.int64)
+    mag, sign = c & 0x7FFF, c & 0x8000
+    cands = np.stack([sign | np.maximum(mag - 1, 0), c, sign | (mag + 1)], 0)   # (neighbours in magnitude, same sign)
+    err = np.abs(W.bf16_bits_to_f64(cands.astype(np.uint16)) - x[None])
+    pick = np.argmin(np.where(err == err.min(0, keepdims=True), cands & 1, 9), 0)
+    return np.take_along_axis(cands, pick[None], 0)[0].astype(np.uint16)
+
+
+@pytest.mark.parametrize("rows", [16, 64, 128])
+def test_reading_of_the_means_against_the_exact_mean(oracle_mod, rows):
+    # The reading fixes HOW the mean is computed (fp32 running sum in row order, fp32 divide, one rounding) so that
+    # its bits do not depend on the implementation.  The plain definition is the exact mean rounded once.  On inputs
+    # of the workloads' kind (N(0,1) rounded to bf16) the fp32 sums of up to 128 bf16 values are exact and the two
+    # agree on every element; with magnitudes spread over many binades they differ in a few elements per 10^5, by
+    # one bf16 ulp.  (The exact sum of bf16 values of bounded exponent range fits fp64.)
+    rng = np.random.default_rng(100 + rows)
+
+    def compare(values):
+        x = W.f32_to_bf16_bits(values.astype(np.float32))
+        got = oracle_mod.pool(x, rows).astype(np.int64)
+        xf = W.bf16_bits_to_f64(x).reshape(x.shape[0], -1, rows, x.shape[-1])
+        exact = _bf16_nearest_even_from_f64(xf.sum(2) / rows).astype(np.int64)
+        return np.abs(got - exact)
+
+    d0 = compare(rng.standard_normal((4, rows * 50, 128)))
+    assert d0.max() == 0, "the two readings differ on N(0,1) inputs: %d of %d" % (np.count_nonzero(d0), d0.size)
+    wide = rng.standard_normal((4, rows * 100, 128)) * np.exp(3.0 * rng.standard_normal((4, rows * 100, 128)))
+    d1 = compare(wide)
+    assert d1.max() <= 1 and np.count_nonzero(d1) <= d1.size // 2000, (np.count_nonzero(d1), d1.size)
+
+
 def test_uniform_scores_keep_lowest_ids(oracle_mod):
     # Q = 0: every key block has probability exactly 1/G; G = 128 and p = 0.75 make the cumulative sums exact
     S, L, d, M, N = 1, 256, 8, 16, 2
