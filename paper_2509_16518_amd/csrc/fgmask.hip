@@ -54,6 +54,14 @@ __device__ __forceinline__ unsigned ordered_bits(float s) {   // monotone: large
   const unsigned u = __float_as_uint(s);
   return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
 }
+// lane-wise arithmetic on the two 16-bit halves of a word
+typedef __attribute__((ext_vector_type(2))) unsigned short u16x2;
+__device__ __forceinline__ unsigned pk_sub_u16(unsigned a, unsigned b) {
+  return __builtin_bit_cast(unsigned, (u16x2)(__builtin_bit_cast(u16x2, a) - __builtin_bit_cast(u16x2, b)));
+}
+__device__ __forceinline__ unsigned pk_min_u16(unsigned a, unsigned b) {
+  return __builtin_bit_cast(unsigned, __builtin_elementwise_min(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
 __device__ __forceinline__ float from_ordered(unsigned o) {
   const unsigned u = o ^ ((o >> 31) ? 0x80000000u : 0xFFFFFFFFu);
   return __uint_as_float(u);
@@ -772,12 +780,13 @@ __global__ void __launch_bounds__(THREADS) select_bins_kernel(const float* score
     if (tid == 0) sh.ncand = 0;
     __syncthreads();
 
-    // pass 1: four consecutive scores per thread and step, four steps in flight; positions past the end get bin
-    // 0xFFFF (below every bin)
+    // pass 1: four consecutive scores per thread and step, four steps in flight while four are processed; the bins go
+    // to LDS in the order of the key blocks; positions past the end get kPastEnd (no bin is as large)
+    constexpr unsigned kPastEnd = 0x7FFFu;
     {
       constexpr int STEP = THREADS * 4;
       auto one = [&](float v, bool valid) -> unsigned {
-        if (!valid) return 0xFFFFu;
+        if (!valid) return kPastEnd;
         const int b = value_bin(v);
         atomicAdd(&sh.mass[b], weight_of(v, rmax));
         return (unsigned)b;
@@ -786,7 +795,6 @@ __global__ void __launch_bounds__(THREADS) select_bins_kernel(const float* score
         const unsigned b0 = one(v.x, true), b1 = one(v.y, j4 + 1 < G), b2 = one(v.z, j4 + 2 < G), b3 = one(v.w, j4 + 3 < G);
         *reinterpret_cast<uint2*>(&shm.bins[j4]) = uint2{b0 | (b1 << 16), b2 | (b3 << 16)};
       };
-      // groups of four steps; the loads of the next group are in flight while this one is processed
       const float4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
       auto load4 = [&](float4 (&x)[4], int j0) {
 #pragma unroll
@@ -807,57 +815,52 @@ __global__ void __launch_bounds__(THREADS) select_bins_kernel(const float* score
     __syncthreads();
     locate_bin<true>(sh, top_p);
 
-    // pass 2 on the bins: one per lane and step, consecutive lanes consecutive key blocks, so that the compare
-    // "bin above the crossing bin" of a wave IS the bit pattern of 64 key blocks.  A wave owns a contiguous stretch
-    // of the row (per_wave key blocks, a multiple of 64), collects its words in two registers (step i -> lanes 2i,
-    // 2i+1) and stores them as two contiguous runs at the end.
+    // pass 2 on the bins, eight per lane and step with 16-bit arithmetic on pairs: bin - crossing bin is negative
+    // for a key block ranked above the crossing bin (it is kept) and zero for a member of it.  The eight sign bits of
+    // a lane make a byte of the row's bits, four lanes a word.  A wave owns a contiguous stretch of the row
+    // (a multiple of 512 key blocks).
     {
       const unsigned b0 = sh.bin;
+      const unsigned b0b0 = b0 | (b0 << 16);
       const int wv = tid >> 6;
-      const int per_wave = ((G + THREADS - 1) / THREADS) * 64;       // <= 4096: at most 64 steps
-      const int k0 = wv * per_wave;                                  // first key block of this wave
-      const int steps = min(per_wave >> 6, max(0, (G - k0 + 63) >> 6));   // of this wave (the same in all lanes)
-      unsigned na = 0;                                               // the same in every lane of a wave
-      uint32_t acc[2] = {0u, 0u};
-      auto one = [&](unsigned b, int i) {
-        const int j = k0 + i * 64 + lane;
-        const bool valid = j < G;
-        const unsigned long long above = __ballot(valid && b < b0);
-        na += (unsigned)__popcll(above);
-        const int r = i >> 5, l2 = (i & 31) * 2;
-        // (lane l2 of the register gets the low word, lane l2 + 1 the high word; value and lane select are scalars)
-        // (two scalar registers cannot both go through the constant bus: the lane select travels in M0)
-        const int sel = __builtin_amdgcn_readfirstlane(l2);
-        const uint32_t lo_w = __builtin_amdgcn_readfirstlane((uint32_t)above), hi_w = __builtin_amdgcn_readfirstlane((uint32_t)(above >> 32));
-        asm volatile("s_mov_b32 m0, %2 ; fg_m0\n\tv_writelane_b32 %0, %1, m0 ; fg_m0" : "+v"(acc[r]) : "s"(lo_w), "s"(sel) : "m0");
-        asm volatile("s_mov_b32 m0, %2 ; fg_m0\n\tv_writelane_b32 %0, %1, m0 ; fg_m0" : "+v"(acc[r]) : "s"(hi_w), "s"(sel + 1) : "m0");
-        if (valid && b == b0) {
-          const unsigned pos = atomicAdd(&sh.ncand, 1u);
-          if (pos < (unsigned)CAP) sh.cand[pos] = (unsigned long long)(unsigned)j;
+      const int per_wave = ((G + THREADS * 8 - 1) / (THREADS * 8)) * 512;   // key blocks per wave
+      const int k0 = wv * per_wave;                                            // first key block of this wave
+      const int steps = min(per_wave >> 9, max(0, (G - k0 + 511) >> 9));       // of this wave (the same in all lanes)
+      unsigned na = 0;
+      for (int i = 0; i < steps; i++) {
+        const int j8 = k0 + i * 512 + lane * 8;   // (below kRowBinsMax: at most G rounded up to 512)
+        const uint4 w = *reinterpret_cast<const uint4*>(&shm.bins[j8]);
+        const unsigned d0 = pk_sub_u16(w.x, b0b0), d1 = pk_sub_u16(w.y, b0b0), d2 = pk_sub_u16(w.z, b0b0), d3 = pk_sub_u16(w.w, b0b0);
+        // word r holds key blocks j8 + 2r (low half) and j8 + 2r + 1: their sign bits go to bits 2r and 16 + 2r
+        unsigned y = (d0 >> 15) & 0x00010001u;
+        y |= (d1 >> 13) & 0x00040004u;
+        y |= (d2 >> 11) & 0x00100010u;
+        y |= (d3 >> 9) & 0x00400040u;
+        unsigned byte = (y & 0x55u) | ((y >> 15) & 0xAAu);         // bit e: key block j8 + e is above the crossing bin
+        const int left = G - j8;                                   // key blocks of this lane inside the row
+        byte = left >= 8 ? byte : (left > 0 ? byte & ((1u << left) - 1u) : 0u);
+        na += (unsigned)__popc(byte);
+        unsigned word = byte << (8 * (lane & 3));
+        word |= __shfl_xor(word, 1);
+        word |= __shfl_xor(word, 2);
+        const int wi = ((k0 + i * 512) >> 5) + (lane >> 2);
+        if ((lane & 3) == 0 && wi < Gw) bits_row[wi] = word;
+        // members: some half of the differences is zero
+        const unsigned m01 = pk_min_u16(d0, d1), m23 = pk_min_u16(d2, d3);
+        const unsigned m = pk_min_u16(m01, m23);
+        if (min(m & 0xFFFFu, m >> 16) == 0u) {
+          const unsigned dd[4] = {d0, d1, d2, d3};
+#pragma unroll
+          for (int e = 0; e < 8; e++) {
+            const unsigned half = (e & 1 ? dd[e >> 1] >> 16 : dd[e >> 1]) & 0xFFFFu;
+            if (half == 0u && e < left) {
+              const unsigned pos = atomicAdd(&sh.ncand, 1u);
+              if (pos < (unsigned)CAP) sh.cand[pos] = (unsigned long long)(unsigned)(j8 + e);
+            }
+          }
         }
-      };
-      // (indices stay below kRowBinsMax: k0 + 64 * steps <= G rounded up to 64)
-      auto half = [&](int r, int i0, int i1) {   // steps [i0, i1) of register r: compile-time register, four reads in flight
-        int i = i0;
-        for (; i + 3 < i1; i += 4) {
-          unsigned b[4];
-#pragma unroll
-          for (int e = 0; e < 4; e++) b[e] = shm.bins[k0 + (i + e) * 64 + lane];
-#pragma unroll
-          for (int e = 0; e < 4; e++) one(b[e], i + e);
-        }
-        for (; i < i1; i++) one(shm.bins[k0 + i * 64 + lane], i);
-        (void)r;
-      };
-      half(0, 0, min(steps, 32));
-      half(1, 32, steps);
-      const int w0 = k0 >> 5;   // first word of this wave
-#pragma unroll
-      for (int r = 0; r < 2; r++) {
-        const int word = w0 + 64 * r + lane;
-        if (lane < 2 * (steps - 32 * r) && word < Gw) bits_row[word] = acc[r];
       }
-      const unsigned long long na_all = block_sum_u64(sh, lane == 0 ? (unsigned long long)na : 0ull);   // (its barriers also order the atomics before the read of ncand)
+      const unsigned long long na_all = block_sum_u64(sh, (unsigned long long)na);   // (its barriers also order the atomics before the read of ncand)
       if (tid == 0) sh.n_above = (unsigned)na_all;
     }
     const unsigned n = sh.ncand;   // (read by all threads after the barriers of the sum)
