@@ -785,14 +785,24 @@ __global__ void __launch_bounds__(THREADS) select_bins_kernel(const float* score
     constexpr unsigned kPastEnd = 0x7FFFu;
     {
       constexpr int STEP = THREADS * 4;
-      auto one = [&](float v, bool valid) -> unsigned {
-        if (!valid) return kPastEnd;
+      auto one = [&](float v) -> unsigned {
         const int b = value_bin(v);
         atomicAdd(&sh.mass[b], weight_of(v, rmax));
         return (unsigned)b;
       };
       auto four = [&](const float4& v, int j4) {
-        const unsigned b0 = one(v.x, true), b1 = one(v.y, j4 + 1 < G), b2 = one(v.z, j4 + 2 < G), b3 = one(v.w, j4 + 3 < G);
+        unsigned b0, b1, b2, b3;
+        if (j4 + 3 < G) {   // (all but the last four of a row whose length is not a multiple of four)
+          b0 = one(v.x);
+          b1 = one(v.y);
+          b2 = one(v.z);
+          b3 = one(v.w);
+        } else {
+          b0 = one(v.x);
+          b1 = j4 + 1 < G ? one(v.y) : kPastEnd;
+          b2 = j4 + 2 < G ? one(v.z) : kPastEnd;
+          b3 = kPastEnd;
+        }
         *reinterpret_cast<uint2*>(&shm.bins[j4]) = uint2{b0 | (b1 << 16), b2 | (b3 << 16)};
       };
       const float4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
