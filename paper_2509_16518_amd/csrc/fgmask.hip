@@ -293,33 +293,6 @@ __device__ __forceinline__ unsigned block_exclusive(unsigned n, unsigned* wave_t
   return before + incl - n;
 }
 
-// Visits every score of a row once, ONE score per lane and step: consecutive lanes hold consecutive key blocks, so
-// a wave-wide vote on a property of the score is the bit pattern of 64 consecutive key blocks.  fn(v, j, valid) is
-// called by all lanes of every wave together, also for positions past the end of the row (valid = j < G), so that
-// it may vote; four steps are in flight.
-template <int THREADS, typename Fn>
-__device__ __forceinline__ void for_each_score_by_lane(const float* s, int G, Fn&& fn) {
-  const int tid = threadIdx.x;
-  int base = 0;
-  for (; base + 3 * THREADS < G; base += 4 * THREADS) {
-    float v[4];
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int j = base + i * THREADS + tid;
-      v[i] = j < G ? s[j] : 0.0f;
-    }
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int j = base + i * THREADS + tid;
-      fn(v[i], j, j < G);
-    }
-  }
-  for (; base < G; base += THREADS) {
-    const int j = base + tid;
-    fn(j < G ? s[j] : 0.0f, j, j < G);
-  }
-}
-
 template <int THREADS, int BINS, int CAP>
 struct SelShared {
   unsigned long long mass[BINS];
@@ -429,9 +402,9 @@ __device__ __forceinline__ void sort_candidates(SH& sh, int n2) {
 // Selection for one query block (row of scores `s`, in device memory or in LDS); called by all threads of the
 // workgroup.  Writes the cut, the count and the kept set as one bit per key block (`keep_bits`, Gw words per row).
 //
-// Passes over the row: (1) histogram of mass over the score range; (2) one score per lane: the scores ranked above
-// the crossing bin are counted and, through wave votes, written as bits straight away, the bin's members are
-// collected; then the members are ranked, and the bits of those at or above the cut are added.  Only a crossing bin
+// Passes over the row: (1) histogram of mass over the score range; (2) the scores ranked above the crossing bin
+// are counted and written as bits straight away, the bin's members are collected; then the members are ranked,
+// and the bits of those at or above the cut are added.  Only a crossing bin
 // with more members than the sort holds takes further passes, and a last one that writes all bits from the cut.
 template <int THREADS, int BINS, int CAP, typename SH>
 __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, float rmax, float rmin, int G, float top_p,
@@ -490,28 +463,48 @@ __device__ __forceinline__ void select_row(SH& sh, const float* s, int64_t row, 
   __syncthreads();
   locate_bin<true>(sh, top_p);
 
-  // One pass, one score per lane: counts the scores ranked above the crossing bin and collects the rank keys of
-  // its members, as many as fit the sort.  cls(v): -1 above the bin, 0 inside, +1 below or outside what was the
-  // bin before.  WITH_BITS: a wave's vote on "above" is the bit pattern of 64 consecutive key blocks, i.e. two words
-  // of the row's bits, which lanes 0 and 1 store (every word of the row is written once, by the wave that owns it).
+  // One pass: counts the scores ranked above the crossing bin and collects the rank keys of its members, as many
+  // as fit the sort.  cls(v): -1 above the bin, 0 inside, +1 below or outside what was the bin before.  WITH_BITS:
+  // "above" of a thread's four consecutive key blocks is a nibble of the row's bits, eight lanes make a word (every
+  // word of the row is written once).  Four 16-byte loads are in flight.
   auto count_and_collect = [&](auto&& cls, auto with_bits) {
     if (tid == 0) sh.ncand = 0;
     __syncthreads();
-    unsigned na = 0;   // the same in every lane of a wave
-    for_each_score_by_lane<THREADS>(s, G, [&](float v, int j, bool valid) {
-      const int c = valid ? cls(v) : 1;
-      const unsigned long long above = __ballot(c < 0);
-      na += (unsigned)__popcll(above);
-      if constexpr (decltype(with_bits)::value) {
-        const int word = ((j - lane) >> 5) + lane;   // (j - lane: the wave's first key block, a multiple of 64)
-        if (lane < 2 && word < Gw) bits_row[word] = lane ? (uint32_t)(above >> 32) : (uint32_t)above;
+    unsigned na = 0;
+    constexpr int STEP = THREADS * 4;
+    const float4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int base = 0; base < Gw * 32; base += 4 * STEP) {   // (the same trip count for all threads: they vote below)
+      float4 v[4];
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const int j4 = base + e * STEP + tid * 4;
+        v[e] = j4 < G ? *reinterpret_cast<const float4*>(s + j4) : zero4;
       }
-      if (c == 0) {
-        const unsigned pos = atomicAdd(&sh.ncand, 1u);
-        if (pos < (unsigned)CAP) sh.cand[pos] = rank_key(v, j);
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const int j4 = base + e * STEP + tid * 4;
+        const float x[4] = {v[e].x, v[e].y, v[e].z, v[e].w};
+        unsigned nib = 0;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const int c = j4 + i < G ? cls(x[i]) : 1;
+          nib |= c < 0 ? 1u << i : 0u;
+          if (c == 0) {
+            const unsigned pos = atomicAdd(&sh.ncand, 1u);
+            if (pos < (unsigned)CAP) sh.cand[pos] = rank_key(x[i], j4 + i);
+          }
+        }
+        na += (unsigned)__popc(nib);
+        if constexpr (decltype(with_bits)::value) {
+          unsigned word = nib << (4 * (tid & 7));
+          word |= __shfl_xor(word, 1);
+          word |= __shfl_xor(word, 2);
+          word |= __shfl_xor(word, 4);
+          if ((tid & 7) == 0 && (j4 >> 5) < Gw) bits_row[j4 >> 5] = word;
+        }
       }
-    });
-    const unsigned long long na_all = block_sum_u64(sh, lane == 0 ? (unsigned long long)na : 0ull);   // (its barriers also order the atomics before the read of ncand)
+    }
+    const unsigned long long na_all = block_sum_u64(sh, (unsigned long long)na);   // (its barriers also order the atomics before the read of ncand)
     if (tid == 0) {
       sh.n_above += (unsigned)na_all;
       sh.bin_cnt = sh.ncand;
