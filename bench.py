@@ -163,6 +163,9 @@ def extra_config(w, steps):
     res["dense"] = dense
     res["sparse_over_dense_time"] = ts["mean"] / dense["%d_row_tiles" % (w.M if w.M in (64, 128) else 128)]["ms"]
     res["sparse_over_fastest_dense_time"] = ts["mean"] / best["ms"]
+    traffic, traffic_src = profiled_traffic(w.name)
+    if traffic is not None:
+        res["traffic"], res["traffic_source"] = traffic, traffic_src
     del r
     torch.cuda.empty_cache()
     return res
