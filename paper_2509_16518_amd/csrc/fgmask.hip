@@ -730,9 +730,9 @@ __global__ void __launch_bounds__(THREADS) select_kernel(const float* scores, co
 }
 
 // Rows of at most kRowBinsMax scores: the row is read from device memory ONCE.  That pass builds the mass histogram
-// and leaves, in LDS, the bin of every score as 16 bits; the second pass then works on those alone (one per lane:
-// bin < crossing bin -> the key block is kept, and a wave's vote is two words of the bit row; bin == crossing bin ->
-// a member, whose score is fetched again by id).  64 KB of bins + the histogram + the members let two 512-thread
+// and leaves, in LDS, the bin of every score as 16 bits; the second pass then works on those alone (eight per lane
+// and step: bin < crossing bin -> the key block is kept, eight such bits are a byte of the bit row; bin == crossing
+// bin -> a member, whose score is fetched again by id).  64 KB of bins + the histogram + the members let two 512-thread
 // workgroups share a compute unit, so the short barrier-separated phases of one row hide under the passes of
 // another; the workgroups are persistent and take rows in turn.  A crossing bin with more members than fit is
 // rare and handed to select_row, which starts that row over from device memory.
@@ -752,7 +752,7 @@ __global__ void __launch_bounds__(THREADS) select_bins_kernel(const float* score
                                                               unsigned long long* cut, unsigned* count, uint32_t* keep_bits,
                                                               int Gw) {
   static_assert(CAP == THREADS, "one member per thread in the ranking");
-  static_assert(BINS >= 128 && BINS % THREADS == 0 && BINS <= 65535, "bins");
+  static_assert(BINS >= 128 && BINS % THREADS == 0 && BINS < 0x7FFF, "bins (16 bits each in LDS, one value set aside)");
   __shared__ BinsShared<THREADS, BINS, CAP> shm;
   auto& sh = shm.sel;
   const int tid = threadIdx.x, lane = tid & 63;
