@@ -208,6 +208,38 @@ def test_batch_and_strided_layout(oracle_mod):
     assert np.array_equal(lse2.double().cpu().numpy(), ref[1])
 
 
+@pytest.mark.parametrize("M,N", [(64, 1), (128, 8)])
+def test_gather_offsets_up_to_the_4_gib_limit(oracle_mod, M, N):
+    """K and V rows one MiB apart: the byte offset of the last row is just below 2^32, the largest the 32-bit
+    gather offsets take (row stride below 16 MiB, last row + 4 KiB inside 4 GiB), and far above 2^31."""
+    L, d, stride_l = 4096, 128, 1 << 19                      # elements: 1 MiB per row
+    assert (L - 1) * stride_l * 2 + 2 * d + 4096 <= 0xFFFFFFFF < L * stride_l * 2 + 2 * d + 4096
+    w = small(M, N, d, L=L, H=1, seed=87)
+    prob = Problem(w)
+
+    def spread(t):   # same values, rows one MiB apart (only the rows themselves are ever written or read)
+        big = torch.empty(L * stride_l, dtype=torch.bfloat16, device="cuda")
+        view = big.as_strided((1, 1, L, d), (L * stride_l, L * stride_l, stride_l, 1))
+        view.copy_(t)
+        return view
+
+    k2, v2 = spread(prob.k), spread(prob.v)
+    p = prob.params(k=k2, v=v2)
+    assert p.k_stride_l == stride_l and p.v_stride_l == stride_l
+    prob.out.view(torch.int16).fill_(0x7FC0)
+    prob.lse.fill_(float("nan"))
+    say("offsets up to 4 GiB M=%d N=%d" % (M, N))
+    F.fgattn_forward(prob.q, k2, v2, prob.d_indptr, prob.d_indices, p, prob.out, prob.lse, prob.workspace(p))
+    torch.cuda.synchronize()
+    got = (out_to_f64(prob.out), prob.lse.double().cpu().numpy())
+    check_against_oracle(oracle_mod, prob, got, what="rows 1 MiB apart")
+    # and bit for bit what the contiguous layout gives
+    ref = prob.run()
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    del k2, v2
+    torch.cuda.empty_cache()
+
+
 def test_zero_query_closed_form_is_exact():
     """Q = 0: all weights are 1/|A| exactly, so out = bf16(mean of active V rows) and lse = ln|A|."""
     w = small(64, 1, 128, L=3000, H=2, seed=91, density=0.4)
