@@ -105,8 +105,10 @@ def check_against_oracle(oracle, prob, got, items=None, what="", scale=None):
     w = prob.w
     if items is None:
         items = np.arange(w.items, dtype=np.int64)
+    # (the C ABI takes scale as a float: the oracle gets the same number, not the double it was rounded from)
     ref_out, ref_lse = oracle.attention(prob.q_bits, prob.k_bits, prob.v_bits, w.M, w.N,
-                                        w.scale if scale is None else scale, prob.indptr, prob.indices, items=items)
+                                        float(np.float32(w.scale if scale is None else scale)), prob.indptr, prob.indices,
+                                        items=items)
     bo, bl = gather_items(w, got[0], got[1], items)
     # rows past L must not have been written: the NaN poison is still there
     assert np.isnan(bl[np.isnan(ref_lse)]).all(), what + ": wrote a row past L"

@@ -23,7 +23,12 @@ EPS = 1e-5
 # Query blocks per test case (keyed by the label and p) whose kept set differed from the oracle's inside the
 # rounding allowance above, as observed on the GPU.  Every case not listed has none and must stay at none: the
 # allowance exists for cumulative sums that pass p within EPS, and is not a blanket budget.
-OBSERVED_ROUNDING_ESCAPES = {}
+OBSERVED_ROUNDING_ESCAPES = {
+    # query block 1986 of the sampled ones: key blocks 42188 and 116081 straddle the cut with scores that are equal
+    # in fp32 (the kernel's ranking precision: it keeps the lower id) and differ in the eighth digit in the oracle's
+    # fp64; the kept sets differ by that one swap
+    "hunyuan p=0.9": 1,
+}
 
 
 def gpu_mask(w, q_bits, k_bits, top_p, scale=None, want_pooled=False, flags=0):
@@ -52,7 +57,9 @@ def gpu_mask(w, q_bits, k_bits, top_p, scale=None, want_pooled=False, flags=0):
 def check_rows(oracle, w, q_bits, k_bits, top_p, indptr, indices, rows, scale=None, what=""):
     """Compares the kept sets of the given query blocks with the oracle; returns the number that differed (validly)."""
     assert indptr[0] == 0 and np.all(np.diff(indptr) >= 1)
-    ref = oracle.topp_rows(q_bits, k_bits, w.M, w.N, w.scale if scale is None else scale, top_p, rows=rows)
+    # (the C ABI takes top_p and scale as floats: the oracle gets the same numbers, not the doubles they were rounded from)
+    ref = oracle.topp_rows(q_bits, k_bits, w.M, w.N, float(np.float32(w.scale if scale is None else scale)),
+                           float(np.float32(top_p)), rows=rows)
     inexact = 0
     for row, (kept, order, cum) in zip(rows, ref):
         got = indices[indptr[row]:indptr[row + 1]]
@@ -242,8 +249,13 @@ def test_mask_full_size_hunyuan(oracle_mod):
     ws = torch.empty(F.fgattn_workspace_bytes(p), dtype=torch.uint8, device="cuda")
     assert F.fgattn_validate_mask(d_indptr, d_indices, p, ws) == 0
     rng = np.random.default_rng(1)
-    rows = sorted({0, w.QB - 1, w.items - 1, int(np.argmax(nnz)), int(np.argmin(nnz))} |
-                  set(rng.choice(w.items, size=11, replace=False).tolist()))
+    # the score buffer holds 17 tiles of 128 query blocks (8 tiles per head, the last one with 33 used rows): the
+    # last row of the first chunk and the first of the second, and the two sides of a head's short last tile
+    tiles_per_head = -(-w.QB // 128)
+    assert tiles_per_head == 8 and (1 << 30) // (128 * 118816 * 4) == 17
+    edge = [2 * w.QB + 127, 2 * w.QB + 128, w.QB - 1, w.QB, 7 * 128 - 1, 7 * 128]
+    rows = sorted({0, w.items - 1, int(np.argmax(nnz)), int(np.argmin(nnz))} | set(edge) |
+                  set(rng.choice(w.items, size=8, replace=False).tolist()))
     bad = check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, what=w.name)
 
 
