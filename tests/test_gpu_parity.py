@@ -240,6 +240,40 @@ def test_gather_offsets_up_to_the_4_gib_limit(oracle_mod, M, N):
     torch.cuda.empty_cache()
 
 
+def test_maximum_sequence_length(oracle_mod):
+    """L = 2^24, the longest sequence the boundary takes (key rows are multiplied as 24-bit numbers): d = 64 keeps a
+    K/V slice at 2 GiB.  131072 query blocks of one head (the ordering pre-pass sorts them by buckets), 48 keys each,
+    with the first and the last key of the sequence in many lists; sampled items against the oracle."""
+    L, M, d, per = 1 << 24, 128, 64, 48
+    w = dataclasses.replace(W.TINY, name="max-L", H=1, L=L, d=d, M=M, N=1, grid=(1, 1, 1), seed=97)
+    say("L = 2^24: generating")
+    q, k, v = W.make_qkv(w)
+    rng = np.random.default_rng(5)
+    items = w.items
+    keys = rng.integers(1, L - 1, size=(items, per), dtype=np.int64)
+    keys[::3, 0] = 0          # the first key ...
+    keys[1::3, 0] = L - 1     # ... and the last one
+    keys.sort(axis=1)
+    # drop the (rare) duplicates inside a list: lists of slightly different lengths
+    lists = [np.unique(row) for row in keys[:4096]]   # (the vectorised construction below is checked against these)
+    keep = np.ones_like(keys, dtype=bool)
+    keep[:, 1:] = keys[:, 1:] != keys[:, :-1]
+    indptr = np.concatenate([[0], np.cumsum(keep.sum(1))]).astype(np.int64)
+    indices = keys[keep].astype(np.int32)
+    assert all(np.array_equal(indices[indptr[i]:indptr[i + 1]], lists[i]) for i in range(0, 4096, 97))
+    prob = Problem(w, q, k, v, mask=(indptr, indices))
+    p = prob.params()
+    assert F.fgattn_validate_mask(prob.d_indptr, prob.d_indices, p, prob.workspace(p)) == 0
+    say("L = 2^24: forward")
+    got = prob.run()
+    picks = np.array(sorted({0, 1, 2, items - 3, items - 2, items - 1} | set(rng.integers(0, items, size=26).tolist())), dtype=np.int64)
+    check_against_oracle(oracle_mod, prob, got, items=picks, what="L = 2^24")
+    # every row's lse is finite (no list is empty) and no row was left unwritten
+    assert np.isfinite(got[1]).all()
+    del prob
+    torch.cuda.empty_cache()
+
+
 def test_zero_query_closed_form_is_exact():
     """Q = 0: all weights are 1/|A| exactly, so out = bf16(mean of active V rows) and lse = ln|A|."""
     w = small(64, 1, 128, L=3000, H=2, seed=91, density=0.4)
