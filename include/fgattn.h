@@ -46,14 +46,15 @@ enum {
 enum {
   /* Scheduling of work items (one item = one query block of one head) onto the persistent
    * workgroups; paper Sec. 4.2 "Load balancing" and Appendix B.  Default (0): per head, items
-   * ordered by decreasing active-list length and fetched from a device-side queue. */
+   * ordered by decreasing active-list length and fetched from device-side queues (one per XCD over a
+   * contiguous share of the heads; a workgroup whose queue is empty takes from the others). */
   FGATTN_FLAG_STATIC_ASSIGN = 1,  /* ablation "no scheduler": item j goes to workgroup j mod grid, natural order */
   FGATTN_FLAG_FIFO_QUEUE = 2,     /* device-side queue, but natural order (no longest-first ordering) */
   FGATTN_FLAG_REUSE_PLAN = 4,     /* skip the ordering pre-pass: `workspace` already holds the order built by an
                                      earlier fgattn_forward/fgattn_plan call for the same mask and params */
-  /* Read by the fgattn_mask_* calls only (the others ignore it): select from the rows of scores in device
-   * memory even where a row fits in LDS (at most 32768 key blocks), the path that longer rows always take.
-   * Same results; pass the same flags to all three mask calls. */
+  /* Read by the fgattn_mask_* calls only (the others ignore it): use the general selection kernel, which reads a
+   * row of scores from device memory in every pass, also for rows of at most 32768 key blocks (which otherwise
+   * take the kernel that reads the row once).  Same results; pass the same flags to all three mask calls. */
   FGATTN_FLAG_MASK_ROWS_IN_HBM = 8,
   /* Read by the fgattn_mask_* calls only: a score buffer of the smallest size (one tile of 128 query blocks)
    * instead of up to 1 GiB, so that small inputs also take several chunks.  Same results; it changes the
