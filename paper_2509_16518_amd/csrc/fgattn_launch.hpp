@@ -27,9 +27,6 @@ int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipS
   }
   long long want = (long long)cus * (wgs_per_cu_cap > 0 && wgs_per_cu_cap < occ_cache[dev] ? wgs_per_cu_cap : occ_cache[dev]);
   lock.unlock();
-#ifdef FG_ONE_WG_PER_CU
-  want = cus;
-#endif
   int grid = (int)(a.n_items < want ? a.n_items : want);
   if (grid < 1) grid = 1;
   if (grid_only) {
