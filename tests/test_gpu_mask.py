@@ -131,6 +131,31 @@ def test_uniform_scores_closed_form(L, N, top_p, kept, flags):
         assert np.array_equal(indices[indptr[r]:indptr[r + 1]], np.arange(kept))
 
 
+@pytest.mark.parametrize("L,flags", [(8192, 0), (8192, F.FLAG_MASK_ROWS_IN_HBM), (40000, 0), (40000, F.FLAG_MASK_ONE_TILE_CHUNKS)])
+def test_clustered_scores_take_the_narrowing_rounds(oracle_mod, L, flags):
+    # Ten key blocks score about ln(0.15 L) (together some 60-80% of the mass), all others within +-0.01 of zero: the
+    # histogram over the score range puts the
+    # whole crowd into one bin, which is also where the mass crosses p -- far more members than the ranking holds
+    # (512 in the kernel that keeps the bins in LDS, which then hands the row over; 2048 in the general kernel), so
+    # the bin is narrowed by re-histogramming its range of score bits and all bits are rewritten from the cut.
+    w = W.Workload("mask-crowd-L%d" % L, H=1, L=L, d=128, M=128, N=1, seed=4400)
+    rng = np.random.default_rng(L)
+    kf = (1e-3 * rng.standard_normal((1, 1, L, w.d))).astype(np.float32)
+    loud = rng.choice(L, size=10, replace=False)
+    kf[0, 0, loud] = np.log(0.15 * L) / 64.0
+    qf = np.empty((1, 1, L, w.d), dtype=np.float32)
+    qf[0, 0] = (0.5 + 0.0002 * (np.arange(L) // w.M))[:, None]
+    q, k = W.f32_to_bf16_bits(qf), W.f32_to_bf16_bits(kf)
+    say("mask crowd L=%d flags=%d" % (L, flags))
+    indptr, indices = gpu_mask(w, q, k, 0.9, scale=1.0, flags=flags)
+    nnz = np.diff(indptr)
+    assert nnz.min() > 2048 and nnz.max() < L - 2048, "the cut is meant to fall inside the crowd"
+    for r in range(w.items):
+        assert np.isin(loud, indices[indptr[r]:indptr[r + 1]]).all()
+    rows = list(range(0, w.items, max(1, w.items // 12))) + [w.items - 1]
+    check_rows(oracle_mod, w, q, k, 0.9, indptr, indices, rows, scale=1.0, what=w.name)
+
+
 def test_dominant_key_block_and_p_one(oracle_mod):
     w = W.Workload("mask-spike", H=1, L=512, d=64, M=32, N=4, seed=4300)
     rng = np.random.default_rng(3)
