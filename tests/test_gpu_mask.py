@@ -221,6 +221,25 @@ def test_mask_feeds_forward(oracle_mod):
     check_against_oracle(oracle_mod, prob, got, what=w.name)
 
 
+def test_emit_with_too_small_a_capacity_drops_the_tail():
+    # a caller that passes fewer entries than the mask holds gets the leading entries and no write past them
+    w = W.Workload("mask-short-capacity", H=2, L=2048, d=64, M=32, N=1, grid=(8, 16, 16), seed=4600)
+    q, k = W.make_qk_local(w, gain=1.5)
+    indptr, indices = gpu_mask(w, q, k, 0.9)
+    dq, dk = to_dev_bf16(q), to_dev_bf16(k)
+    p = F.make_params(dq, dk, dk, dq, w.M, w.N, w.scale)
+    ws = torch.empty(F.fgattn_mask_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    d_indptr = torch.empty(w.items + 1, dtype=torch.int64, device="cuda")
+    F.fgattn_mask_select(dq, dk, p, 0.9, d_indptr, ws)
+    nnz = indices.size
+    for cap in (nnz - 1, nnz // 2, 1, 0):
+        buf = torch.full((nnz + 8,), -7, dtype=torch.int32, device="cuda")
+        F.fgattn_mask_emit(p, d_indptr, buf[:cap], ws)
+        torch.cuda.synchronize()
+        got = buf.cpu().numpy()
+        assert np.array_equal(got[:cap], indices[:cap]) and (got[cap:] == -7).all(), cap
+
+
 def test_mask_argument_checks():
     w = W.TINY
     q, k, _ = W.make_qkv(w)
