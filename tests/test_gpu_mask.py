@@ -221,6 +221,33 @@ def test_mask_feeds_forward(oracle_mod):
     check_against_oracle(oracle_mod, prob, got, what=w.name)
 
 
+@pytest.mark.parametrize("flags", [0, F.FLAG_MASK_ROWS_IN_HBM], ids=["bins-in-lds", "rows-in-hbm"])
+def test_p_one_keeps_what_the_fixed_point_resolves(oracle_mod, flags):
+    # top_p = 1 on peaked rows: weights are 2^-40 fixed point relative to the row maximum, so a key block more than
+    # 40 ln 2 = 27.7 below the maximum weighs nothing and is dropped (all of them together hold less than G * 2^-40
+    # of the mass); the fp64 oracle keeps every key block.  Everything within 27 of the maximum must be kept,
+    # nothing further than 27.8 below it may be.
+    w = W.Workload("mask-p-one-peaked", H=2, L=3000, d=64, M=32, N=1, grid=(1, 1, 3000), seed=4700)
+    q, k = W.make_qk_local(w, gain=3.0, bandwidth=0.02)
+    say("mask p = 1, peaked rows, flags=%d" % flags)
+    indptr, indices = gpu_mask(w, q, k, 1.0, flags=flags)
+    rows = list(range(w.items))
+    ref = oracle_mod.topp_rows(q, k, w.M, w.N, float(np.float32(w.scale)), 1.0, rows=rows)
+    dropped_somewhere = 0
+    for row, (kept, order, cum) in zip(rows, ref):
+        prob = np.empty(w.G)
+        prob[order] = np.diff(np.concatenate([[0.0], cum]))
+        below_max = np.log(prob.max()) - np.log(np.maximum(prob, 1e-300))   # score distance to the row maximum
+        inside = np.zeros(w.G, dtype=bool)
+        inside[indices[indptr[row]:indptr[row + 1]]] = True
+        assert inside[below_max <= 27.0].all(), "row %d: a key block with weight was dropped" % row
+        assert not inside[below_max >= 27.8].any(), "row %d: a key block without weight was kept" % row
+        assert prob[~inside].sum() < w.G * 2.0 ** -40
+        dropped_somewhere += int((~inside).any())
+    say("    %d of %d rows drop weightless key blocks" % (dropped_somewhere, w.items))
+    assert dropped_somewhere > 0, "the inputs were meant to have rows with key blocks below the resolution"
+
+
 def test_emit_with_too_small_a_capacity_drops_the_tail():
     # a caller that passes fewer entries than the mask holds gets the leading entries and no write past them
     w = W.Workload("mask-short-capacity", H=2, L=2048, d=64, M=32, N=1, grid=(8, 16, 16), seed=4600)
