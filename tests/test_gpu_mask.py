@@ -367,3 +367,36 @@ def test_mask_degenerate_sizes(oracle_mod, M, N, L, top_p):
     say("mask %s p=%.2f" % (w.name, top_p))
     indptr, indices = gpu_mask(w, q, k, top_p)
     check_rows(oracle_mod, w, q, k, top_p, indptr, indices, list(range(w.items)), what=w.name)
+
+
+def _wide_random_mask_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for c in range(n):
+        M = int(rng.choice([16, 32, 64, 128]))
+        d = int(rng.choice([64, 128]))
+        N = int(rng.choice([1, 1, 1, 2, 3, 8, 17, 32, 64]))
+        L = int(rng.integers(1, 6000))
+        H = int(rng.integers(1, 5))
+        top_p = float(rng.choice([0.1, 0.3, 0.5, 0.7, 0.9, 0.99]))
+        gain = float(rng.choice([0.0, 1.0, 2.0, 3.0]))
+        flags = int(rng.choice([0, 0, 8, 16, 24]))
+        cases.append((M, N, d, L, H, top_p, gain, flags, 15000 + c))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,d,L,H,top_p,gain,flags,seed", _wide_random_mask_cases(48, 20251129))
+def test_mask_seeded_random_shapes_wide(oracle_mod, M, N, d, L, H, top_p, gain, flags, seed):
+    # a wider draw than test_mask_seeded_random_shapes: longer sequences, more values of p, both selection kernels and
+    # the one-tile score buffer; every query block against the oracle (sampled ones where that is too many scores)
+    w = W.Workload("mask-wide-M%d-N%d-d%d-L%d-s%d" % (M, N, d, L, seed), H=H, L=L, d=d, M=M, N=N, grid=(1, 1, L), seed=seed)
+    if gain > 0.0:
+        q, k = W.make_qk_local(w, gain=gain, bandwidth=0.02)
+    else:
+        q, k, _ = W.make_qkv(w)
+    say("mask %s H=%d p=%.2f gain=%.1f flags=%d" % (w.name, H, top_p, gain, flags))
+    indptr, indices = gpu_mask(w, q, k, top_p, flags=flags)
+    rows = list(range(w.items))
+    if w.items * w.G > 3e6:
+        rows = sorted(set(np.random.default_rng(seed).integers(0, w.items, size=20).tolist()) | {0, w.items - 1})
+    check_rows(oracle_mod, w, q, k, top_p, indptr, indices, rows, what=w.name)

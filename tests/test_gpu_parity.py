@@ -317,3 +317,34 @@ def test_seeded_random_shapes(oracle_mod, M, N, d, L, H, kind, density, seed):
     p = prob.params()
     assert F.fgattn_validate_mask(prob.d_indptr, prob.d_indices, p, prob.workspace(p)) == 0
     check_against_oracle(oracle_mod, prob, prob.run(), what=w.name)
+
+
+def _wide_random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for c in range(n):
+        M = int(rng.choice([16, 32, 64, 128]))
+        d = int(rng.choice([64, 128]))
+        N = int(rng.choice([1, 1, 1, 2, 3, 4, 7, 8, 16, 31, 32, 64, 128, 200]))
+        L = int(rng.integers(1, 5000))
+        H = int(rng.integers(1, 10))
+        B = int(rng.choice([1, 1, 2]))
+        kind = [W.MASK_RANDOM, W.MASK_SKEW_LEN, W.MASK_WINDOW_FILL][int(rng.integers(0, 3))]
+        density = float(rng.choice([0.02, 0.1, 0.3, 0.7, 1.0]))
+        flags = int(rng.choice([0, 0, F.FLAG_STATIC_ASSIGN, F.FLAG_FIFO_QUEUE]))
+        skew = float(rng.choice([0.0, 0.5, 1.0]))
+        span = int(rng.integers(1, 40))
+        cases.append((M, N, d, L, H, B, kind, density, flags, skew, span, 12000 + c))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,d,L,H,B,kind,density,flags,skew,span,seed", _wide_random_cases(64, 20251128))
+def test_seeded_random_shapes_wide(oracle_mod, M, N, d, L, H, B, kind, density, flags, skew, span, seed):
+    """A wider draw than test_seeded_random_shapes: up to nine heads (more and fewer than the eight queues), B = 2,
+    the three mask generators, densities from 2% to all keys, the three scheduling modes; every row against the oracle."""
+    w = dataclasses.replace(small(M, N, d, L=L, H=H, kind=kind, density=density, seed=seed, skew=skew), B=B)
+    if kind == W.MASK_WINDOW_FILL:
+        w = dataclasses.replace(w, grid=(1, 1, L), window=(0, 0, span))
+    say("wide random shape %s H=%d B=%d kind=%d density=%.2f flags=%d" % (w.name, H, B, kind, density, flags))
+    prob = Problem(w)
+    check_against_oracle(oracle_mod, prob, prob.run(flags=flags), what=w.name)
