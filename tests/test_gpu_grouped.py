@@ -167,3 +167,38 @@ def test_grouping_argument_checks():
     with pytest.raises(F.FgattnError) as e:
         F.fgattn_group_select(prob.d_indptr, prob.d_indices, p, F.GROUP_XOR, tiles, up, ws[:512])
     assert e.value.code == F.E_WORKSPACE
+
+
+def _random_group_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for c in range(n):
+        M = int(rng.choice([16, 32, 64]))
+        d = int(rng.choice([64, 128]))
+        N = int(rng.choice([1, 1, 2, 3, 8, 16, 32, 64]))
+        L = int(rng.integers(1, 4000))
+        H = int(rng.integers(1, 4))
+        B = int(rng.choice([1, 1, 2]))
+        kind = [W.MASK_RANDOM, W.MASK_SKEW_LEN, W.MASK_WINDOW_FILL][int(rng.integers(0, 3))]
+        density = float(rng.choice([0.05, 0.3, 0.6]))
+        mode = ["consecutive", "xor"][int(rng.integers(0, 2))]
+        cases.append((M, N, d, L, H, B, kind, density, mode, 6700 + c))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,d,L,H,B,kind,density,mode,seed", _random_group_cases(32, 20251130))
+def test_grouping_seeded_random_shapes(oracle_mod, M, N, d, L, H, B, kind, density, mode, seed):
+    # shapes nobody picked by hand: the device pre-pass must equal the grouping oracle bit for bit, and the grouped
+    # forward pass on its output must agree with the attention oracle on the UNGROUPED mask
+    import dataclasses
+    w = W.Workload("group-rand-M%d-N%d-d%d-L%d" % (M, N, d, L), H=H, L=L, d=d, M=M, N=N, grid=(1, 1, L), window=(0, 0, 9),
+                   kind=kind, density=density, seed=seed, skew=0.7)
+    w = dataclasses.replace(w, B=B)
+    prob = Problem(w)
+    say("grouping random %s H=%d B=%d kind=%d density=%.2f %s" % (w.name, H, B, kind, density, mode))
+    got = gpu_grouping(prob, mode)
+    ref = GR.grouped_mask(prob.indptr, prob.indices, w.B * w.H, w.QB, w.G, 128 // M, mode)
+    for a, b, name in zip(got, ref, ("group_tiles", "union_indptr", "union_indices", "union_members")):
+        assert np.array_equal(a, b), name
+    out = run_grouped(prob, *got)
+    check_against_oracle(oracle_mod, prob, out, what=w.name + " " + mode)
