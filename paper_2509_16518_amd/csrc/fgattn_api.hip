@@ -251,7 +251,7 @@ static int run_forward(const void* q, const void* k, const void* v, const int64_
   a.memb = group_memb;
   a.tile_rows = p->M;
   a.R = R;
-  const int NT = a.M <= 32 ? 128 : a.M == 64 ? 64 : 32;   // keys per LDS tile of the variant launched for M
+  const int NT = a.M <= 32 ? 32 : a.M == 64 ? 64 : 32;   // keys per LDS tile of the variant launched for M
   a.nt_div_n = NT / a.N;
   a.nt_mod_n = NT % a.N;
   a.n_recip16 = (65536u + (uint32_t)a.N - 1) / (uint32_t)a.N;

@@ -19,10 +19,12 @@
 // per-lane scalars plus one exchange between lanes l and l^32, and the probabilities are
 // already laid out as the B operand of the second MFMA: P never moves between lanes.
 //
-// Every wave owns a 32-query x 32-key piece of each tile.  A workgroup covers MT = 32, 64 or
-// 128 query rows with RW = MT/32 waves along the rows and KW = 4/RW waves along the keys of a
+// Every wave owns a 32-query x 32-key piece of each tile.  A workgroup of WV waves covers MT = 32, 64 or
+// 128 query rows with RW = MT/32 waves along the rows and KW = WV/RW waves along the keys of a
 // tile (NT = 32*KW keys); waves that split the keys keep private (max, sum, O) and merge once
-// per work item.
+// per work item.  WV is 4 except for the 32-row tile, which runs as single-wave workgroups: a wave's K and V
+// slots take 32 KB at d = 128, so LDS admits five waves per compute unit, and five independent workgroups use
+// them all (a four-wave workgroup would leave it at four).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -112,16 +114,16 @@ constexpr int clcm(int a, int b) { return a / cgcd(a, b) * b; }
 // workgroup reads K(t+1) and V(t-1) and gathers K(t+KS) and V(t+VS-2) into the slots that the previous iteration
 // released, so KS-1 K tiles and VS-1 V tiles can be in flight.  The forward pass is instantiated with two slots each
 // (deeper rings make the gather half alone faster -- a third K slot by 8% -- but not the whole kernel); the
-// measurement aid also builds the gather half with a K ring of three.
-template <int MT, int D, int KS = 2, int VS = 2>
+// measurement aid also builds the gather half with a K ring of three.  WV = waves of a workgroup.
+template <int MT, int D, int KS = 2, int VS = 2, int WV = 4>
 struct FwdCfg {
   static constexpr int RW = MT / 32;            // waves along query rows (32 rows each)
-  static constexpr int KW = 4 / RW;             // waves along keys within a tile (32 keys each)
+  static constexpr int KW = WV / RW;            // waves along keys within a tile (32 keys each)
   static constexpr int NT = 32 * KW;            // keys per LDS tile
   static constexpr int CH = D / 8;              // 16-byte chunks per row
   static constexpr int ROWB = D * 2;            // bytes per K or V row
   static constexpr int RPI = 64 / CH;           // rows fetched by one wave-wide 16 B/lane load
-  static constexpr int RPW = NT / 4;            // rows of a tile each wave fetches
+  static constexpr int RPW = NT / WV;           // rows of a tile each wave fetches
   static constexpr int IPW = RPW / RPI;         // load instructions per wave, per tile, per tensor
   static constexpr int SSTEPS = D / 16;         // MFMA steps along d for S^T
   static constexpr int DBLK = D / 32;           // 32-row blocks of O^T
@@ -136,6 +138,7 @@ struct FwdCfg {
   static constexpr int LDS_BYTES_BIAS = BIAS_OFF + 2 * NT * 4 + 16;
   static constexpr int NKEYSETS = KS - VS + 3;  // key-row sets alive at once: tiles t+VS-2 (V gather) .. t+KS (K gather)
   static_assert(MT == 32 || MT == 64 || MT == 128, "query tile");
+  static_assert(WV >= RW && WV % RW == 0 && (WV == 1 || WV == 2 || WV == 4), "waves of a workgroup");
   static_assert(D == 64 || D == 128, "head dim");
   static_assert(KS >= 2 && VS >= 2 && KS >= VS, "ring depths");
   static_assert(IPW >= 1 && RPW % RPI == 0 && (RPW & (RPW - 1)) == 0, "loader shape");
@@ -199,9 +202,9 @@ enum { PART_ALL = 0, PART_GATHER = 1, PART_COMPUTE = 2 };
 constexpr bool variant_has_mask_row(int nmode, bool grouped) {
   return grouped || nmode == NMODE_GROUPS_SHORT;
 }
-template <int MT, int D, int NMODE, bool GROUPED = false, int KS = 2, int VS = 2>
+template <int MT, int D, int NMODE, bool GROUPED = false, int KS = 2, int VS = 2, int WV = 4>
 constexpr int fwd_lds_bytes() {
-  using C = FwdCfg<MT, D, KS, VS>;
+  using C = FwdCfg<MT, D, KS, VS, WV>;
   return variant_has_mask_row(NMODE, GROUPED) ? C::LDS_BYTES_BIAS : C::RING_BYTES;
 }
 
@@ -228,9 +231,9 @@ __device__ __forceinline__ void wait_vmem_le(int& loaded) {   // the same, and `
 // them, listed in a.group_tiles) that shares one gathered key list -- the union of the members' lists -- while
 // every member attends only to its own key blocks: a.memb holds, per entry of the union list, the bit mask of the
 // members that selected it, and scores of the others are set to -inf before the softmax.
-template <int MT, int D, int NMODE, int OCC, int PART = PART_ALL, bool GROUPED = false, int KS = 2, int VS = 2>
-__global__ void __launch_bounds__(256, OCC) fgattn_fwd_kernel(const FwdArgs a) {
-  using C = FwdCfg<MT, D, KS, VS>;
+template <int MT, int D, int NMODE, int OCC, int PART = PART_ALL, bool GROUPED = false, int KS = 2, int VS = 2, int WV = 4>
+__global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs a) {
+  using C = FwdCfg<MT, D, KS, VS, WV>;
   constexpr bool DENSE = NMODE == NMODE_DENSE;
   constexpr bool WAVE_PRIO = NMODE == NMODE_DENSE || NMODE == NMODE_N1;
   constexpr bool MASK_ROWS = variant_has_mask_row(NMODE, GROUPED);   // per-key bias / membership row in LDS

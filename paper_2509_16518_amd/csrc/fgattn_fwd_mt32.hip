@@ -1,27 +1,32 @@
 // Forward-kernel instantiations for the 32-row query tile: d = 64 / 128; dense, one key per
-// group, N keys per group.
+// group, N keys per group.  Single-wave workgroups (32 keys per tile): see FwdCfg.
 #include "fgattn_fwd.hpp"
 #include "fgattn_launch.hpp"
 
 namespace fg {
 
-static_assert(FwdCfg<32, 128>::NT == (32 <= 32 ? 128 : 32 == 64 ? 64 : 32), "host-side NT table out of date");
+static_assert(FwdCfg<32, 128, 2, 2, 1>::NT == (32 <= 32 ? 32 : 32 == 64 ? 64 : 32), "host-side NT table out of date");
 
-template <int D, int OCC>
+// WPS: waves per SIMD the register budget is set for (d = 128: two, 256 registers; d = 64: three)
+template <int D, int WPS>
 static int launch_d(const FwdArgs& a, int cus, hipStream_t stream, int* grid_only) {
   static int occ[4][64];
   if (a.indptr == nullptr)
-    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_DENSE, OCC>, fwd_lds_bytes<32, D, NMODE_DENSE>(), a, cus, stream, grid_only, occ[0]);
+    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_DENSE, WPS, PART_ALL, false, 2, 2, 1>,
+                          fwd_lds_bytes<32, D, NMODE_DENSE, false, 2, 2, 1>(), a, cus, stream, grid_only, occ[0], 0, 64);
   if (a.N == 1)
-    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_N1, OCC>, fwd_lds_bytes<32, D, NMODE_N1>(), a, cus, stream, grid_only, occ[1]);
+    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_N1, WPS, PART_ALL, false, 2, 2, 1>,
+                          fwd_lds_bytes<32, D, NMODE_N1, false, 2, 2, 1>(), a, cus, stream, grid_only, occ[1], 0, 64);
   if (a.N > 0 && a.L % a.N == 0)
-    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_GROUPS, OCC>, fwd_lds_bytes<32, D, NMODE_GROUPS>(), a, cus, stream, grid_only, occ[2]);
-  return launch_variant(fgattn_fwd_kernel<32, D, NMODE_GROUPS_SHORT, OCC>, fwd_lds_bytes<32, D, NMODE_GROUPS_SHORT>(), a, cus, stream, grid_only, occ[3]);
+    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_GROUPS, WPS, PART_ALL, false, 2, 2, 1>,
+                          fwd_lds_bytes<32, D, NMODE_GROUPS, false, 2, 2, 1>(), a, cus, stream, grid_only, occ[2], 0, 64);
+  return launch_variant(fgattn_fwd_kernel<32, D, NMODE_GROUPS_SHORT, WPS, PART_ALL, false, 2, 2, 1>,
+                        fwd_lds_bytes<32, D, NMODE_GROUPS_SHORT, false, 2, 2, 1>(), a, cus, stream, grid_only, occ[3], 0, 64);
 }
 
 int launch_mt32(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only) {
-  if (d == 64) return launch_d<64, 2>(a, cus, stream, grid_only);
-  return launch_d<128, 1>(a, cus, stream, grid_only);
+  if (d == 64) return launch_d<64, 3>(a, cus, stream, grid_only);
+  return launch_d<128, 2>(a, cus, stream, grid_only);
 }
 
 }  // namespace fg

@@ -11,7 +11,7 @@ namespace fg {
 
 template <typename Kernel>
 int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipStream_t stream, int* grid_only,
-                   int* occ_cache, int wgs_per_cu_cap = 0) {
+                   int* occ_cache, int wgs_per_cu_cap = 0, int threads = 256) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FGATTN_E_DEVICE;
   static std::mutex cache_mutex;   // one per kernel variant: first calls from several host threads take turns
@@ -21,7 +21,7 @@ int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipS
                             lds_bytes) != hipSuccess)
       return FGATTN_E_DEVICE;
     int occ = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, 256, lds_bytes) != hipSuccess || occ < 1)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, threads, lds_bytes) != hipSuccess || occ < 1)
       return FGATTN_E_DEVICE;
     occ_cache[dev] = occ;
   }
@@ -33,7 +33,7 @@ int launch_variant(Kernel kernel, int lds_bytes, const FwdArgs& a, int cus, hipS
     *grid_only = grid;
     return FGATTN_OK;
   }
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds_bytes, stream, a);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds_bytes, stream, a);
   return hipGetLastError() == hipSuccess ? FGATTN_OK : FGATTN_E_DEVICE;
 }
 
