@@ -7,15 +7,17 @@ namespace fg {
 
 static_assert(FwdCfg<32, 128, 2, 2, 1>::NT == (32 <= 32 ? 32 : 32 == 64 ? 64 : 32), "host-side NT table out of date");
 
-// WPS: waves per SIMD the register budget is set for (d = 128: two, 256 registers; d = 64: three)
-template <int D, int WPS>
+// WPS: waves per SIMD the register budget is set for.  d = 128: two (256 registers; LDS admits five waves per CU
+// anyway).  d = 64 (16 KB of LDS per wave): three for the one-key-per-group variant (ten waves per CU, a few spilled
+// registers) and two for the others, whose loaders need more registers -- as measured, 3-5% either way.
+template <int D, int WPS_N1, int WPS>
 static int launch_d(const FwdArgs& a, int cus, hipStream_t stream, int* grid_only) {
   static int occ[4][64];
   if (a.indptr == nullptr)
     return launch_variant(fgattn_fwd_kernel<32, D, NMODE_DENSE, WPS, PART_ALL, false, 2, 2, 1>,
                           fwd_lds_bytes<32, D, NMODE_DENSE, false, 2, 2, 1>(), a, cus, stream, grid_only, occ[0], 0, 64);
   if (a.N == 1)
-    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_N1, WPS, PART_ALL, false, 2, 2, 1>,
+    return launch_variant(fgattn_fwd_kernel<32, D, NMODE_N1, WPS_N1, PART_ALL, false, 2, 2, 1>,
                           fwd_lds_bytes<32, D, NMODE_N1, false, 2, 2, 1>(), a, cus, stream, grid_only, occ[1], 0, 64);
   if (a.N > 0 && a.L % a.N == 0)
     return launch_variant(fgattn_fwd_kernel<32, D, NMODE_GROUPS, WPS, PART_ALL, false, 2, 2, 1>,
@@ -25,8 +27,8 @@ static int launch_d(const FwdArgs& a, int cus, hipStream_t stream, int* grid_onl
 }
 
 int launch_mt32(const FwdArgs& a, int d, int cus, hipStream_t stream, int* grid_only) {
-  if (d == 64) return launch_d<64, 3>(a, cus, stream, grid_only);
-  return launch_d<128, 2>(a, cus, stream, grid_only);
+  if (d == 64) return launch_d<64, 3, 2>(a, cus, stream, grid_only);
+  return launch_d<128, 2, 2>(a, cus, stream, grid_only);
 }
 
 }  // namespace fg
