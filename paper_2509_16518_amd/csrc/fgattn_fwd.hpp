@@ -94,11 +94,10 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {
   return (unsigned)(uintptr_t)((FG_LDS const unsigned char*)p);
 }
 
-__device__ __forceinline__ float lane_pair_max(float x) {
-  // lanes l and l^32 hold the two halves of one query's key set
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
+// (three-input maximum, written so that the compiler selects v_max3_f32.  Not inline assembly: the compiler does not
+// insert the wait states an MFMA result needs before a vector instruction reads it when that instruction is hidden
+// in an asm statement)
+__device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 __device__ __forceinline__ float lane_pair_sum(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
@@ -177,11 +176,13 @@ __device__ __forceinline__ void softmax_max(f32x16& S, const float* bias_keys, i
 #pragma unroll
       for (int e = 0; e < 4; e++) S[4 * r4 + e] = (8 * r4 + e) < limit ? S[4 * r4 + e] : -INFINITY;
   }
-  float mx = fmaxf(S[0], S[1]);
-#pragma unroll
-  for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(S[r], S[r + 1]));
-  mx = lane_pair_max(mx);
-  m_new = fmaxf(m_run, mx);
+  // 16 scores -> 1 in eight three-input maxima, three levels deep (this phase is a serial dependency of the key loop)
+  const float t0 = max3(S[0], S[1], S[2]), t1 = max3(S[3], S[4], S[5]), t2 = max3(S[6], S[7], S[8]);
+  const float t3 = max3(S[9], S[10], S[11]), t4 = max3(S[12], S[13], S[14]);
+  const float mx = fmaxf(max3(t0, t1, t2), max3(t3, t4, S[15]));
+  // lanes l and l^32 hold the two halves of one query's key set
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+  m_new = max3(__uint_as_float(r[0]), __uint_as_float(r[1]), m_run);
 }
 
 // NMODE selects how a compacted key position maps to a key row:
@@ -610,7 +611,17 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
     f32x16 SA, SB;             // S^T of even / odd tiles (one is turned into P while the other accumulates)
     i32x4 PA[2], PB[2];        // P^T (packed bf16 pairs) of even / odd tiles: B operands of the second MFMA
     float m_run = -INFINITY;   // exponent base (raw score units) of this lane's query; lags the true max lazily
-    float l_run = 0.0f;        // this lane's partial sum of exponentials
+    float l_run = 0.0f, l_run2 = 0.0f;   // this lane's partial sum of exponentials, in two chains (even / odd scores)
+    // derived from the exponent base whenever it moves (set_base), so that the key loop computes neither per tile:
+    float neg_mc = 0.0f;           // -m_run * c_log2, 0 while m_run is -inf: the additive term of the exponent
+    float m_move = -INFINITY;      // a running max above this moves the base: m_run + kLazyLog2 / c_log2 (-inf while m_run is)
+    const float lazy_raw = kLazyLog2 / a.c_log2;
+    auto set_base = [&](float m) {
+      const bool none = m == -INFINITY;   // no valid key seen yet
+      m_run = m;
+      neg_mc = none ? 0.0f : -m * a.c_log2;
+      m_move = none ? -INFINITY : m + lazy_raw;
+    };
     float m_pend = -INFINITY;  // running max including the tile in S
     bool resc = false;         // wave-uniform: the tile in S moves the exponent base (O, l must be rescaled)
 
@@ -641,9 +652,6 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
       constexpr bool GATHER = decltype(with_gather)::value;
       constexpr bool QK = decltype(with_qk)::value && PART != PART_GATHER;   // also Sn = K(slot krd) Q^T
       constexpr bool EXP = decltype(with_exp)::value && PART != PART_GATHER;  // also P = exp2(c*(So - m)) -> Pout, row sum
-      const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;   // a wave that has seen no valid key yet
-      const float neg_mc = -m_safe * a.c_log2;
-      float psum0 = 0.0f, psum1 = 0.0f;
       const unsigned char* vst = smem + C::V_OFF + vrd * C::TENSOR_BYTES;
       const unsigned char* kst = smem + C::K_OFF + krd * C::TENSOR_BYTES;
       auto read_kf = [&](int s) {
@@ -679,8 +687,8 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
             // scale = 0), so their p is exactly 0 without a select
             const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(So[r], a.c_log2, neg_mc));
             const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(So[r + 1], a.c_log2, neg_mc));
-            psum0 += p0;
-            psum1 += p1;
+            l_run += p0;
+            l_run2 += p1;
             f32x2 pp = {p0, p1};
             int pk = __builtin_bit_cast(int, __builtin_convertvector(pp, bf16x2));
             asm volatile("" : "+v"(pk));   // keeps the compiler from sinking the conversion out of the slot
@@ -711,7 +719,6 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
         slot(std::integral_constant<int, 6>());
         slot(std::integral_constant<int, 7>());
       }
-      if (EXP) l_run += psum0 + psum1;
     };
     // Phase Y, vector ALU only in the key loop: the row max of the new scores Sn (tile Tm) and the rare decision to
     // move the exponent base (see kLazyLog2).  With MFMA (prologue only) it first computes Sn = K Q^T with K in slot
@@ -750,7 +757,7 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
       }
       if constexpr (LAZY_BIAS) slot_dirty[Tm & 1] |= masked;
       m_pend = m_new;
-      const bool lane_moves = (m_run == -INFINITY) ? (m_new > m_run) : ((m_new - m_run) * a.c_log2 > kLazyLog2);
+      const bool lane_moves = m_new > m_move;   // (the first valid key of a lane also moves it: m_move = -inf until then)
       resc = __builtin_amdgcn_ballot_w64(lane_moves) != 0;
     };
     auto rotate_keys = [&]() {
@@ -784,7 +791,8 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
       if (__builtin_expect(resc, 0)) {   // the exponent base moves: l now, O after the MFMAs of the old base
         alpha = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f((m_run - m_pend) * a.c_log2);
         l_run *= alpha;
-        m_run = m_pend;
+        l_run2 *= alpha;
+        set_base(m_pend);
       }
       // ids requested IDL iterations ago -> key rows (with untracked id loads the cross-lane permute was already
       // issued before the barrier, at the end of the previous iteration, and only its result is consumed here)
@@ -861,7 +869,7 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
       __syncthreads();
       // S(0) from K slot 0
       y_phase(std::integral_constant<int, 0>(), 0, SA, yes());
-      m_run = m_pend;   // O = 0 and l = 0 so far: the first exponent base needs no rescale
+      set_base(m_pend);   // O = 0 and l = 0 so far: the first exponent base needs no rescale
       resc = false;
       int t = 0;
       for (;;) {
@@ -892,7 +900,7 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
     }
 
     // ---------------- epilogue ----------------
-    float l_tot = lane_pair_sum(l_run);
+    float l_tot = lane_pair_sum(l_run + l_run2);
     if (C::KW > 1) {
       __syncthreads();   // every wave is done with the tile buffers
       float* scratch = reinterpret_cast<float*>(smem);
