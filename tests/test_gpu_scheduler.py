@@ -67,6 +67,17 @@ def test_output_is_bitwise_independent_of_scheduling(oracle_mod):
     assert np.array_equal(base[0], again[0]) and np.array_equal(base[1], again[1])   # run-to-run determinism
 
 
+@pytest.mark.parametrize("M,N,d", [(16, 1, 128), (32, 8, 64), (64, 1, 128), (128, 1, 128), (128, 8, 64), (128, 1, 64)])
+def test_repeated_runs_are_bitwise_identical_for_every_tiling(M, N, d):
+    # every tile shape, ten runs under three schedules: a result that depended on timing (an instruction reading a
+    # matrix-core result before it has landed, a slot read before its gather was waited for) would differ somewhere
+    prob = Problem(skewed(M=M, N=N, d=d, L=8192 + 40, H=4, seed=31 + M))
+    first = prob.run()
+    for i in range(9):
+        other = prob.run(flags=(0, F.FLAG_STATIC_ASSIGN, F.FLAG_FIFO_QUEUE)[i % 3])
+        assert np.array_equal(first[0], other[0]) and np.array_equal(first[1], other[1]), (i, M, N, d)
+
+
 def test_reuse_plan_and_queue_rewind():
     """The kernel rewinds the queue when it drains, so the stored order can be replayed without a pre-pass."""
     prob = Problem(skewed(H=2, L=4096))
