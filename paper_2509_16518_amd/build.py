@@ -44,6 +44,48 @@ def check_m0_writes(asm_path):
                                    (asm_path, n, line.strip()))
 
 
+def check_inline_asm_hazards(asm_path):
+    """Vector-memory instructions written as inline assembly (the LDS-DMA gathers, the untracked id loads) get none of
+    the wait states the compiler inserts for hardware hazards.  The one that could apply to them: a vector-ALU
+    instruction that writes a scalar register (v_readfirstlane, v_readlane, a compare with a scalar destination) must be
+    five wait states ahead of a vector-memory instruction that reads that register as its base.  The kernels keep such
+    bases in scalar registers from the start, so no such write should be anywhere near; this scan fails the build if
+    one ever is."""
+    import re
+    sreg = re.compile(r"\bs\[(\d+):(\d+)\]|\bs(\d+)\b")
+    window = []   # (wait states this instruction contributes, scalar registers a vector-ALU instruction writes)
+    with open(asm_path) as f:
+        for n, line in enumerate(f, 1):
+            code = line.split(";", 1)[0].strip()
+            if not code or code.startswith(".") or code.endswith(":"):
+                continue
+            op = code.split()[0]
+            if op.startswith("global_load") or op.startswith("global_store"):
+                m = sreg.search(code.split(None, 1)[1]) if " " in code else None
+                if m:
+                    lo, hi = (int(m.group(1)), int(m.group(2))) if m.group(1) else (int(m.group(3)), int(m.group(3)))
+                    states = 0
+                    for w, written in reversed(window):
+                        if states >= 5:
+                            break
+                        if any(lo <= r <= hi for r in written):
+                            raise RuntimeError("%s:%d: a vector-ALU write of s%s is only %d wait states ahead of %s" %
+                                               (asm_path, n, sorted(written), states, code))
+                        states += w
+            written = set()
+            if op.startswith("v_"):
+                first = code.split(None, 1)[1].split(",")[0] if " " in code else ""
+                m = sreg.fullmatch(first.strip())
+                if m:
+                    written = set(range(int(m.group(1)), int(m.group(2)) + 1)) if m.group(1) else {int(m.group(3))}
+            states = 1
+            if op == "s_nop":
+                states = int(code.split()[1], 0) + 1
+            window.append((states, written))
+            if len(window) > 8:
+                window.pop(0)
+
+
 def build_hip(force=True, extra_flags=()):
     """Compile every .hip translation unit for gfx950 (in parallel) and link libfgattn.so in-tree."""
     from concurrent.futures import ThreadPoolExecutor
@@ -60,6 +102,7 @@ def build_hip(force=True, extra_flags=()):
     for f in sorted(os.listdir(objdir)):
         if f.endswith("-gfx950.s"):
             check_m0_writes(os.path.join(objdir, f))
+            check_inline_asm_hazards(os.path.join(objdir, f))
         elif not f.endswith(".o"):
             os.remove(os.path.join(objdir, f))   # other intermediates of -save-temps
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIBFGATTN])

@@ -108,6 +108,23 @@ def test_build_rejects_a_foreign_m0_write(tmp_path):
         build.check_m0_writes(str(bad))
 
 
+def test_build_rejects_a_scalar_base_written_too_close_to_a_gather(tmp_path):
+    # a vector-ALU write of a scalar register needs five wait states before a vector-memory instruction reads it; the
+    # compiler pads its own instructions but not the ones inside asm statements
+    far = tmp_path / "far.s"
+    far.write_text("\tv_readfirstlane_b32 s4, v1\n\ts_nop 4\n\tglobal_load_lds_dwordx4 v2, s[4:5]\n"
+                   "\tv_readfirstlane_b32 s8, v1\n\ts_mov_b32 m0, s9 ; fg_m0\n\tglobal_load_lds_dwordx4 v2, s[4:5] offset:1024\n")
+    build.check_inline_asm_hazards(str(far))
+    near = tmp_path / "near.s"
+    near.write_text("\tv_readfirstlane_b32 s5, v1\n\ts_mov_b32 m0, s9 ; fg_m0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v2, s[4:5]\n")
+    with pytest.raises(RuntimeError, match="wait states ahead"):
+        build.check_inline_asm_hazards(str(near))
+    pair = tmp_path / "pair.s"
+    pair.write_text("\tv_cmp_lt_f32_e64 s[6:7], v1, v2\n\tv_mov_b32_e32 v3, v4\n\tglobal_load_dword v5, v6, s[6:7]\n")
+    with pytest.raises(RuntimeError, match="wait states ahead"):
+        build.check_inline_asm_hazards(str(pair))
+
+
 def test_mask_workspace_is_bounded(lib):
     # the fp32 scores pass through a buffer of at most 1 GiB (whole tiles of 128 query blocks); what grows with the
     # problem is one bit per pair of query block and key block, the block means and 20 bytes per query block
