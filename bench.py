@@ -272,7 +272,18 @@ def main():
                                                           "4_waves_2_tile_rings": per_cu(ms_one)},
                 "frac_bf16_mfma_peak_if_gather_bound": {"2_tile_rings": useful / ms_gather / 1e9 / MFMA_BF16_PEAK_TFLOPS,
                                                         "3_tile_k_ring": useful / ms_ring3 / 1e9 / MFMA_BF16_PEAK_TFLOPS}})
-        del scratch_out, scratch_lse
+        # the instruction-issue ceiling of the compute half: the same mix of MFMAs, exponentials and other vector
+        # instructions per wave-tile as this tile shape's key loop, on the same occupancy, without memory traffic or barriers
+        other = 69 if w.M == 64 else 63
+        probe_scratch = torch.empty(2048 * torch.cuda.get_device_properties(0).multi_processor_count, dtype=torch.uint8, device="cuda")
+        probe_flop = F.fgattn_issue_probe(other, 4000, probe_scratch)
+        ms_mix = time_calls(lambda: F.fgattn_issue_probe(other, 4000, probe_scratch), 3, 10)["median"]
+        ms_mfma = time_calls(lambda: F.fgattn_issue_probe(0, 4000, probe_scratch), 3, 10)["median"]
+        res["parts"]["issue_ceiling"] = {
+            "mix_per_wave_tile": "16 MFMA + 16 v_exp + %d other vector instructions" % other,
+            "tflops_mfma_only": probe_flop / ms_mfma / 1e9, "tflops_at_this_mix": probe_flop / ms_mix / 1e9,
+            "compute_only_over_ceiling": (useful / ms_compute) / (probe_flop / ms_mix)}
+        del scratch_out, scratch_lse, probe_scratch
     if args.mask and w.grid[0] * w.grid[1] * w.grid[2] == w.L and w.name == "wan-1.3b":
         # the step before the hot path (Sec. 4.3): top-p mask from block means, on Q/K with space-time locality
         log("timing the top-p mask kernels")

@@ -343,6 +343,17 @@ int fgattn_forward_part(const void* q, const void* k, const void* v, const int64
   return fg::run_forward(q, k, v, mask_indptr, mask_indices, p, out, lse, workspace, workspace_bytes, stream, part);
 }
 
+int fgattn_issue_probe(int other_valu_per_16_mfma, int iters, void* scratch, size_t scratch_bytes, double* flop, void* stream) {
+  if (!scratch || !flop) return FGATTN_E_NULL;
+  if (iters < 1 || iters > (1 << 20)) return FGATTN_E_SHAPE;
+  fg::DeviceInfo dev;
+  int rc = fg::device_info(&dev);
+  if (rc) return rc;
+  if (scratch_bytes < (size_t)2 * dev.cus * 256 * sizeof(float)) return FGATTN_E_WORKSPACE;
+  *flop = 2.0 * dev.cus * 4 * (double)iters * 16 * 32768.0;
+  return fg::launch_issue_probe(other_valu_per_16_mfma, iters, static_cast<float*>(scratch), dev.cus, static_cast<hipStream_t>(stream));
+}
+
 int fgattn_forward_grouped(const void* q, const void* k, const void* v, const int32_t* group_tiles,
                            const int64_t* union_indptr, const int32_t* union_indices, const uint8_t* union_members,
                            const fgattn_params* p, void* out, float* lse, void* workspace, size_t workspace_bytes,

@@ -38,6 +38,10 @@ int launch_forward(const FwdArgs& a, int d, int cus, hipStream_t stream, int* gr
 // Gather-only (part = 1) or compute-only (part = 2) instantiation of the M = 64, d = 128, N = 1 variant.
 int launch_part(const FwdArgs& a, int part, int cus, hipStream_t stream);
 
+// Measurement aid: 16 MFMAs + 16 exponentials + `other` ordinary vector instructions per loop trip on 2 * cus workgroups
+// of four waves; `out` takes 2 * cus * 256 floats.
+int launch_issue_probe(int other, int iters, float* out, int cus, hipStream_t stream);
+
 // Grouped query tiles: the 128-row variant with membership masks (d = 64 / 128; N = 1 or N > 1).
 int launch_grouped(const FwdArgs& a, int d, int cus, hipStream_t stream);
 

@@ -50,6 +50,8 @@ def lib():
         L.fgattn_forward_static.restype = ctypes.c_int
         L.fgattn_forward_part.argtypes = [vp, vp, vp, i64p, vp, pp, vp, vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
         L.fgattn_forward_part.restype = ctypes.c_int
+        L.fgattn_issue_probe.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), vp]
+        L.fgattn_issue_probe.restype = ctypes.c_int
         L.fgattn_forward_grouped.argtypes = [vp, vp, vp, vp, i64p, vp, vp, pp, vp, vp, vp, ctypes.c_size_t, vp]
         L.fgattn_forward_grouped.restype = ctypes.c_int
         L.fgattn_dense_forward.argtypes = [vp, vp, vp, pp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -142,6 +144,14 @@ def fgattn_forward_part(q, k, v, mask_indptr, mask_indices, params, out, lse, wo
                                      mask_indices.data_ptr(), ctypes.byref(params), out.data_ptr(), lse.data_ptr(),
                                      workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(part),
                                      _stream_ptr(stream)))
+
+
+def fgattn_issue_probe(other_valu_per_16_mfma, iters, scratch, stream=None):
+    """Measurement aid: enqueues the instruction-issue probe; returns the MFMA FLOP count of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(lib().fgattn_issue_probe(int(other_valu_per_16_mfma), int(iters), scratch.data_ptr(),
+                                    scratch.numel() * scratch.element_size(), ctypes.byref(flop), _stream_ptr(stream)))
+    return flop.value
 
 
 def fgattn_dense_forward(q, k, v, params, out, lse, workspace, stream=None):

@@ -93,6 +93,21 @@ def test_forward_part_is_a_measurement_aid_only(M):
     assert torch.equal(a, prob.out)
 
 
+def test_issue_probe_is_a_measurement_aid_only():
+    # runs for the instruction mixes it is built for, touches only its scratch, rejects everything else
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    scratch = torch.zeros(2048 * cus + 64, dtype=torch.uint8, device="cuda")
+    scratch[2048 * cus:] = 0x5A
+    for other in (0, 59, 63, 69):
+        flop = F.fgattn_issue_probe(other, 8, scratch[:2048 * cus])
+        assert flop == 2.0 * cus * 4 * 8 * 16 * 32768.0
+    torch.cuda.synchronize()
+    assert bool((scratch[2048 * cus:] == 0x5A).all())
+    expect(F.E_FLAGS, lambda: F.fgattn_issue_probe(7, 8, scratch))
+    expect(F.E_WORKSPACE, lambda: F.fgattn_issue_probe(69, 8, scratch[:1024]))
+    expect(F.E_SHAPE, lambda: F.fgattn_issue_probe(69, 0, scratch))
+
+
 @pytest.mark.parametrize("M,N,L", [(64, 1, 32760), (128, 32, 32760), (128, 32, 32768), (16, 8, 1000)])
 def test_grid_size_is_reported_for_every_variant(M, N, L):
     q = torch.empty((1, 2, L, 128), dtype=torch.bfloat16, device="cuda")
