@@ -214,8 +214,10 @@ constexpr int fwd_lds_bytes() {
 // wait for every gather in flight: the counter is shared and the compiler cannot see the gathers.)  The kernel waits
 // with the s_waitcnt that precedes each tile's barrier (wait_vmem_le(loaded) ties the register to that wait for the compiler);
 // consumers clamp what they read to [0, L), so even a register read too early could never address out of bounds.
-__device__ __forceinline__ void load_id_untracked(int& dst, const int32_t* src) {
-  asm volatile("global_load_dword %0, %1, off" : "=v"(dst) : "v"(src) : "memory");
+__device__ __forceinline__ void load_id_untracked(int& dst, const int32_t* base, unsigned byte_off) {
+  // (scalar base + 32-bit per-lane offset: no 64-bit address arithmetic on the vector ALU)
+  base = static_cast<const int32_t*>(pin_scalar(base));
+  asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(byte_off), "s"(base) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmem_le() {   // s_waitcnt vmcnt(N): at most N vector-memory loads still in flight
@@ -377,7 +379,8 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
     }
     const int total = cnt * N;  // compacted key positions (a short last group leaves invalid ones)
     const int ntiles = (total + C::NT - 1) / C::NT;
-    const int32_t* idx = DENSE ? nullptr : a.indices + beg;
+    // (wave-uniform; pinned to scalar registers here, an item's set-up ahead of the first id load that uses it as its base)
+    const int32_t* idx = DENSE ? nullptr : static_cast<const int32_t*>(pin_scalar(a.indices + beg));
     // Row that padded / out-of-range positions of a tile fetch (their scores are masked out): the item's first
     // active key, so that only rows of the active set are ever multiplied, even by zero (0 x Inf would be NaN).
     int pad_key = 0;
@@ -415,6 +418,7 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
     constexpr int KNEW = C::NKEYSETS - 1;
     int tq = 0, tr = 0;   // (T*NT) / N and (T*NT) % N for the next tile to fetch ids for, advanced without divisions
     const int lpos = wv * C::RPW + lrow;
+    const unsigned id_lane4 = (unsigned)(wv * C::RPW + (lane & (C::RPW - 1))) * 4u;   // byte offset of this lane's id inside a tile's ids
     const int last = ntiles - 1;
     const uint8_t* memb = GROUPED ? a.memb + beg : nullptr;
     // a tile whose positions need checking: short last group, ragged last tile, or (GROUPED) always, since the mask
@@ -436,7 +440,7 @@ __global__ void __launch_bounds__(WV * 64, OCC) fgattn_fwd_kernel(const FwdArgs 
       if (NMODE == NMODE_DENSE) return;
       if constexpr (ASM_IDS) {
         // (the position is clamped into the list: a ragged last tile masks what lies past the end by position)
-        load_id_untracked(wdst, idx + min(T * C::NT + wv * C::RPW + (lane & (C::RPW - 1)), cnt - 1));
+        load_id_untracked(wdst, idx, min((unsigned)(T * C::NT * 4) + id_lane4, (unsigned)(cnt - 1) * 4u));
         return;
       }
       if (__builtin_expect(coalesced_ids(T), 1)) {
