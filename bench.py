@@ -274,7 +274,7 @@ def main():
                                                         "3_tile_k_ring": useful / ms_ring3 / 1e9 / MFMA_BF16_PEAK_TFLOPS}})
         # the instruction-issue ceiling of the compute half: the same mix of MFMAs, exponentials and other vector
         # instructions per wave-tile as this tile shape's key loop, on the same occupancy, without memory traffic or barriers
-        other = 69 if w.M == 64 else 63
+        other = 67 if w.M == 64 else 61
         probe_scratch = torch.empty(2048 * torch.cuda.get_device_properties(0).multi_processor_count, dtype=torch.uint8, device="cuda")
         probe_flop = F.fgattn_issue_probe(other, 4000, probe_scratch)
         ms_mix = time_calls(lambda: F.fgattn_issue_probe(other, 4000, probe_scratch), 3, 10)["median"]

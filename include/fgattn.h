@@ -232,7 +232,7 @@ int fgattn_forward_part(const void* q, const void* k, const void* v, const int64
  * the forward kernel's occupancy (two four-wave workgroups per compute unit), a loop of 16 MFMAs (32x32x16 bf16), 16
  * exponentials and `other_valu_per_16_mfma` ordinary vector instructions per trip, `iters` trips, no memory traffic:
  * what a SIMD sustains on the mix of one wave-tile of the key loop (Sec. 2's softmax between the two matrix products).
- * Built for other_valu_per_16_mfma = 69 (64-row sparse tile), 63 (128-row sparse tile), 59 (128-row dense tile), and 0 =
+ * Built for other_valu_per_16_mfma = 67 (64-row sparse tile), 61 (128-row sparse tile), 59 (128-row dense tile), and 0 =
  * the MFMAs alone, without the exponentials; anything else gives FGATTN_E_FLAGS.  `scratch`: device memory, at least 2048 B per compute unit (results nobody
  * reads); *flop (host) receives the MFMA FLOP count of the launch, so that FLOP / measured time is the ceiling.
  * Asynchronous on `stream`. */

@@ -74,8 +74,8 @@ int launch_issue_probe(int other, int iters, float* out, int cus, hipStream_t st
     return hipGetLastError() == hipSuccess ? FGATTN_OK : FGATTN_E_DEVICE;
   };
   if (other == 59) return go(issue_probe_kernel<59>);
-  if (other == 63) return go(issue_probe_kernel<63>);
-  if (other == 69) return go(issue_probe_kernel<69>);
+  if (other == 61) return go(issue_probe_kernel<61>);
+  if (other == 67) return go(issue_probe_kernel<67>);
   if (other == 0) return go(issue_probe_kernel<0>);
   return FGATTN_E_FLAGS;
 }

@@ -98,14 +98,14 @@ def test_issue_probe_is_a_measurement_aid_only():
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     scratch = torch.zeros(2048 * cus + 64, dtype=torch.uint8, device="cuda")
     scratch[2048 * cus:] = 0x5A
-    for other in (0, 59, 63, 69):
+    for other in (0, 59, 61, 67):
         flop = F.fgattn_issue_probe(other, 8, scratch[:2048 * cus])
         assert flop == 2.0 * cus * 4 * 8 * 16 * 32768.0
     torch.cuda.synchronize()
     assert bool((scratch[2048 * cus:] == 0x5A).all())
     expect(F.E_FLAGS, lambda: F.fgattn_issue_probe(7, 8, scratch))
-    expect(F.E_WORKSPACE, lambda: F.fgattn_issue_probe(69, 8, scratch[:1024]))
-    expect(F.E_SHAPE, lambda: F.fgattn_issue_probe(69, 0, scratch))
+    expect(F.E_WORKSPACE, lambda: F.fgattn_issue_probe(67, 8, scratch[:1024]))
+    expect(F.E_SHAPE, lambda: F.fgattn_issue_probe(67, 0, scratch))
 
 
 @pytest.mark.parametrize("M,N,L", [(64, 1, 32760), (128, 32, 32760), (128, 32, 32768), (16, 8, 1000)])
